@@ -1,0 +1,164 @@
+/*
+ * dsqconv.h -- C ABI of libdsqconv: b-bit (2..4) uniformly quantized conv2d
+ * executed as integer arithmetic on codes, for AMD MI355X (gfx950).
+ *
+ * The three calls are the deployment form of one DSQ-quantized convolution
+ * layer (paper: Algorithm 1, feed-forward, after the soft quantizer has been
+ * hardened by the sign function -- Sec. 3.2 -- so that it is the uniform
+ * quantizer of Sec. 3.1; Sec. 3.5 "Training and Deploying" and Sec. 4.5 run
+ * such layers with integer GEMM kernels):
+ *
+ *   dsq_pack_weights   once per layer   w -> codes (Alg. 1 steps 1,3 for w),
+ *                                       laid out for the matrix cores
+ *   dsq_quantize_act   per activation   a -> codes (Alg. 1 steps 1,3 for a)
+ *   dsq_conv2d         per layer        o = Convolution(w_hat, a_hat)
+ *                                       (Alg. 1 steps 4,5) as an integer GEMM
+ *                                       on the codes plus zero-point terms
+ *
+ * Conventions for every call
+ *   - All tensor pointers are DEVICE memory owned by the caller; scalars and
+ *     the descriptor struct are host values.  The library allocates nothing,
+ *     keeps no state and never synchronises: work is enqueued on `hip_stream`
+ *     (a hipStream_t passed as void*, NULL = default stream) and the call
+ *     returns at once.
+ *   - Arguments are validated on the host before anything is launched; on any
+ *     error nothing has been enqueued.  Errors are return codes only.
+ *   - Device pointers must be 16-byte aligned.
+ *   - bits is 2, 3 or 4, the same for activations and weights of one layer.
+ *
+ * Quantizer (Sec. 3.1 uniform quantizer with range [l,u]; tie rule from
+ * sgn(0)=+1 applied at the interval midpoints m_i of Sec. 3.2), evaluated in
+ * IEEE binary32 in exactly this order:
+ *     Delta = (u - l) / (2^b - 1)            (true division)
+ *     v     = min(max(x, l), u)              (NaN -> l)
+ *     t     = (v - l) / Delta                (true division)
+ *     code  = clamp((int)floor(t + 0.5), 0, 2^b - 1)
+ * The level a code stands for is l + Delta*code (Alg. 1 step 4).
+ *
+ * Packed code format ("container" = 4 bits for b in {3,4}, 2 bits for b=2)
+ *   A 32-bit word holds 8 (4-bit) or 16 (2-bit) consecutive channels
+ *   c0, c1, ...; byte j (j=0..3) of the word is
+ *       4-bit:  c[j] | c[j+4] << 4
+ *       2-bit:  c[j] | c[j+4] << 2 | c[j+8] << 4 | c[j+12] << 6
+ *   so (word >> k*container) & 0x0F0F0F0F (or 0x03030303) yields four
+ *   consecutive channels as four int8.
+ *   Activations: [N][H][W][Cp] with Cp = C rounded up to a multiple of 64,
+ *   channels >= C hold code 0; one pixel is Cp*container/8 bytes.
+ *   Weights: blocks of 16 output channels x 64 input channels of one filter
+ *   tap, ordered [Cop/16][Cp/64][R*S][64 lanes], lane = 16*g + (o % 16)
+ *   holding channels 64*cb + 16*g + 0..15 of output channel o (2 words at
+ *   4-bit, 1 word at 2-bit).  Cop = C_out rounded up to a multiple of 256;
+ *   rows >= C_out and channels >= C_in hold code 0.
+ */
+#ifndef DSQCONV_H
+#define DSQCONV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DSQ_OK = 0,
+    DSQ_ERR_NULL = 1,        /* a required pointer is NULL */
+    DSQ_ERR_BITS = 2,        /* bits not in {2,3,4} */
+    DSQ_ERR_RANGE = 3,       /* !(l < u) or a bound is not finite */
+    DSQ_ERR_SHAPE = 4,       /* a dimension <= 0, or Ho/Wo <= 0 */
+    DSQ_ERR_UNSUPPORTED = 5, /* R != S, R not in {1,3}, stride not in {1,2},
+                                pad > R-1, a tensor of 2^31 or more elements,
+                                unknown layout */
+    DSQ_ERR_ALIGN = 6,       /* device pointer not 16-byte aligned */
+    DSQ_ERR_SIZE = 7,        /* a caller buffer is smaller than required */
+    DSQ_ERR_HIP = 8          /* the HIP runtime refused a launch */
+} dsq_status;
+
+typedef enum { DSQ_NHWC = 0, DSQ_NCHW = 1 } dsq_layout;
+
+typedef struct {
+    int N, C_in, H, W;   /* input activation */
+    int C_out, R, S;     /* filter bank (R = S) */
+    int stride, pad;
+    int bits;
+} dsq_conv_desc;
+
+/* ---- sizes (pure host functions; 0 on invalid arguments) ---------------- */
+
+/* Bytes of the packed activation tensor for an N x H x W x C input. */
+size_t dsq_act_packed_bytes(int N, int H, int W, int C, int bits);
+/* Bytes of the packed weight tensor. */
+size_t dsq_wgt_packed_bytes(int C_out, int C_in, int R, int S, int bits);
+/* Bytes of the per-output-channel side table written by dsq_pack_weights:
+ * float delta_w[Cop], float l_w[Cop], int32 sw_total[Cop],
+ * int32 sw_tap[Cop][R*S]  (sums of weight codes over C_in). */
+size_t dsq_wgt_aux_bytes(int C_out, int R, int S);
+
+/* ---- dsq_quantize_act: Alg. 1 steps 1 and 3 for the activation ---------
+ * x            device, float32, N*C*H*W elements in `layout`
+ * l, u         the learned clip range of this activation (host scalars)
+ * codes_packed device, out, dsq_act_packed_bytes() bytes (codes_bytes is the
+ *              caller's buffer size and is checked)
+ * pix_code_sum device, out, int32[N*H*W]: sum over channels of the codes of
+ *              each pixel (the conv epilogue needs it for the l_w term)
+ */
+dsq_status dsq_quantize_act(const float *x, dsq_layout layout, int N, int C,
+                            int H, int W, float l, float u, int bits,
+                            void *codes_packed, size_t codes_bytes,
+                            int32_t *pix_code_sum, void *hip_stream);
+
+/* ---- dsq_pack_weights: Alg. 1 steps 1 and 3 for the weights ------------
+ * w_oihw       device, float32 [C_out][C_in][R][S]; may be NULL if
+ *              codes_oihw is given
+ * l_w, u_w     device, float32 [C_out]: clip range per output channel (a
+ *              per-tensor range is the case of equal entries).  Always
+ *              required (they define the levels).  A channel whose range is
+ *              not finite or not l<u gets delta_w = NaN, which makes that
+ *              channel's outputs NaN; validate ranges on the host if needed.
+ * codes_oihw   device, uint8 [C_out][C_in][R][S] or NULL.  If non-NULL the
+ *              quantizer is skipped and these codes (must be < 2^bits) are
+ *              packed as they are.
+ * w_packed     device, out, dsq_wgt_packed_bytes() bytes
+ * w_aux        device, out, dsq_wgt_aux_bytes() bytes
+ */
+dsq_status dsq_pack_weights(const float *w_oihw, const float *l_w,
+                            const float *u_w, const uint8_t *codes_oihw,
+                            int C_out, int C_in, int R, int S, int bits,
+                            void *w_packed, size_t w_bytes, void *w_aux,
+                            size_t aux_bytes, void *hip_stream);
+
+/* ---- dsq_conv2d: Alg. 1 steps 4 and 5 ----------------------------------
+ * Computes, for every output pixel m = (n, oy, ox) and output channel o,
+ *     ACC   = sum over taps (r,s) inside the image, channels c of
+ *             code_a[n, oy*stride-pad+r, ox*stride-pad+s, c] * code_w[o,c,r,s]
+ *     out   = Da*Dw[o]*ACC + l_a*Dw[o]*SW + l_w[o]*Da*SA + KV*l_a*l_w[o]
+ * with SA / SW the sums of activation / weight codes over the same in-image
+ * taps and KV = C_in * (number of in-image taps): exactly the convolution of
+ * the dequantized tensors with zero padding.  ACC is exact int32; the four
+ * terms are combined in binary64 and rounded once to binary32.
+ *
+ * d            geometry and bits (host struct)
+ * act_packed, pix_code_sum   outputs of dsq_quantize_act for this input
+ * l_a, u_a     the same range that was given to dsq_quantize_act
+ * w_packed, w_aux            outputs of dsq_pack_weights for this layer
+ * out          device, float32, N*Ho*Wo*C_out elements in `out_layout`
+ * acc_or_null  device, int32, same shape and layout as out, or NULL: raw ACC
+ */
+dsq_status dsq_conv2d(const dsq_conv_desc *d, const void *act_packed,
+                      const int32_t *pix_code_sum, float l_a, float u_a,
+                      const void *w_packed, const void *w_aux, float *out,
+                      dsq_layout out_layout, int32_t *acc_or_null,
+                      void *hip_stream);
+
+/* Selects the convolution kernel: 0 = automatic (default), 1 = the simple
+ * one-wave-per-tile kernel, 2 = the LDS-patch kernel.  For tests and
+ * benchmarking; process-wide, not thread-safe.  Returns the previous value. */
+int dsq_set_conv_kernel(int which);
+
+/* Static, NUL-terminated description of a status code. */
+const char *dsq_status_string(dsq_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DSQCONV_H */

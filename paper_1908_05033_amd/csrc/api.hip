@@ -1,0 +1,147 @@
+// C ABI of libdsqconv (see include/dsqconv.h): host-side validation and
+// dispatch only; every step of the path runs in the HIP kernels.
+#include <math.h>
+
+#include "../../include/dsqconv.h"
+#include "dsq_device.h"
+#include "dsq_kernels.h"
+
+namespace {
+
+int g_conv_kernel = 0;   // 0 auto, 1 simple, 2 patch
+
+bool bits_ok(int bits) { return bits >= 2 && bits <= 4; }
+bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
+bool range_ok(float l, float u) { return isfinite(l) && isfinite(u) && l < u; }
+const long long kMaxElems = (1LL << 31) - 1;
+
+}  // namespace
+
+extern "C" {
+
+size_t dsq_act_packed_bytes(int N, int H, int W, int C, int bits)
+{
+    if (N <= 0 || H <= 0 || W <= 0 || C <= 0 || !bits_ok(bits)) return 0;
+    return (size_t)N * H * W * (size_t)(dsq_round_up(C, 64) * dsq_container(bits) / 8);
+}
+
+size_t dsq_wgt_packed_bytes(int C_out, int C_in, int R, int S, int bits)
+{
+    if (C_out <= 0 || C_in <= 0 || R <= 0 || S <= 0 || !bits_ok(bits)) return 0;
+    return (size_t)dsq_round_up(C_out, 256) * R * S *
+           (size_t)(dsq_round_up(C_in, 64) * dsq_container(bits) / 8);
+}
+
+size_t dsq_wgt_aux_bytes(int C_out, int R, int S)
+{
+    if (C_out <= 0 || R <= 0 || S <= 0) return 0;
+    return (size_t)dsq_round_up(C_out, 256) * (3 + (size_t)R * S) * 4;
+}
+
+dsq_status dsq_quantize_act(const float *x, dsq_layout layout, int N, int C, int H, int W, float l,
+                            float u, int bits, void *codes_packed, size_t codes_bytes,
+                            int32_t *pix_code_sum, void *hip_stream)
+{
+    if (!x || !codes_packed || !pix_code_sum) return DSQ_ERR_NULL;
+    if (!bits_ok(bits)) return DSQ_ERR_BITS;
+    if (!range_ok(l, u)) return DSQ_ERR_RANGE;
+    if (N <= 0 || C <= 0 || H <= 0 || W <= 0) return DSQ_ERR_SHAPE;
+    if (layout != DSQ_NHWC && layout != DSQ_NCHW) return DSQ_ERR_UNSUPPORTED;
+    if ((long long)N * H * W * dsq_round_up(C, 64) > kMaxElems) return DSQ_ERR_UNSUPPORTED;
+    if (layout == DSQ_NCHW && N > 65535) return DSQ_ERR_UNSUPPORTED;
+    if (!aligned16(x) || !aligned16(codes_packed) || !aligned16(pix_code_sum)) return DSQ_ERR_ALIGN;
+    if (codes_bytes < dsq_act_packed_bytes(N, H, W, C, bits)) return DSQ_ERR_SIZE;
+    hipError_t e = dsq_launch_quantize_act(x, layout == DSQ_NCHW, N, C, H, W, l, u, bits,
+                                           codes_packed, pix_code_sum, (hipStream_t)hip_stream);
+    return e == hipSuccess ? DSQ_OK : DSQ_ERR_HIP;
+}
+
+dsq_status dsq_pack_weights(const float *w_oihw, const float *l_w, const float *u_w,
+                            const uint8_t *codes_oihw, int C_out, int C_in, int R, int S, int bits,
+                            void *w_packed, size_t w_bytes, void *w_aux, size_t aux_bytes,
+                            void *hip_stream)
+{
+    if ((!w_oihw && !codes_oihw) || !l_w || !u_w || !w_packed || !w_aux) return DSQ_ERR_NULL;
+    if (!bits_ok(bits)) return DSQ_ERR_BITS;
+    if (C_out <= 0 || C_in <= 0 || R <= 0 || S <= 0) return DSQ_ERR_SHAPE;
+    if (R != S || (R != 1 && R != 3)) return DSQ_ERR_UNSUPPORTED;
+    if ((long long)dsq_round_up(C_out, 256) * dsq_round_up(C_in, 64) * R * S > kMaxElems)
+        return DSQ_ERR_UNSUPPORTED;
+    if (!aligned16(w_packed) || !aligned16(w_aux)) return DSQ_ERR_ALIGN;
+    if (w_bytes < dsq_wgt_packed_bytes(C_out, C_in, R, S, bits)) return DSQ_ERR_SIZE;
+    if (aux_bytes < dsq_wgt_aux_bytes(C_out, R, S)) return DSQ_ERR_SIZE;
+    hipError_t e = dsq_launch_pack_weights(w_oihw, l_w, u_w, codes_oihw, C_out, C_in, R, bits,
+                                           w_packed, w_aux, (hipStream_t)hip_stream);
+    return e == hipSuccess ? DSQ_OK : DSQ_ERR_HIP;
+}
+
+dsq_status dsq_conv2d(const dsq_conv_desc *d, const void *act_packed, const int32_t *pix_code_sum,
+                      float l_a, float u_a, const void *w_packed, const void *w_aux, float *out,
+                      dsq_layout out_layout, int32_t *acc_or_null, void *hip_stream)
+{
+    if (!d || !act_packed || !pix_code_sum || !w_packed || !w_aux || !out) return DSQ_ERR_NULL;
+    if (!bits_ok(d->bits)) return DSQ_ERR_BITS;
+    if (!range_ok(l_a, u_a)) return DSQ_ERR_RANGE;
+    if (d->N <= 0 || d->C_in <= 0 || d->H <= 0 || d->W <= 0 || d->C_out <= 0 || d->R <= 0 ||
+        d->S <= 0 || d->stride <= 0 || d->pad < 0)
+        return DSQ_ERR_SHAPE;
+    if (d->R != d->S || (d->R != 1 && d->R != 3) || (d->stride != 1 && d->stride != 2) ||
+        d->pad > d->R - 1)
+        return DSQ_ERR_UNSUPPORTED;
+    if (out_layout != DSQ_NHWC && out_layout != DSQ_NCHW) return DSQ_ERR_UNSUPPORTED;
+    if (d->H + 2 * d->pad < d->R || d->W + 2 * d->pad < d->S) return DSQ_ERR_SHAPE;
+    const int Ho = (d->H + 2 * d->pad - d->R) / d->stride + 1;
+    const int Wo = (d->W + 2 * d->pad - d->S) / d->stride + 1;
+    if (Ho <= 0 || Wo <= 0) return DSQ_ERR_SHAPE;
+    const int Cp = dsq_round_up(d->C_in, 64), Cop = dsq_round_up(d->C_out, 256);
+    if ((long long)d->N * d->H * d->W * Cp > kMaxElems) return DSQ_ERR_UNSUPPORTED;
+    if ((long long)d->N * Ho * Wo * d->C_out > kMaxElems) return DSQ_ERR_UNSUPPORTED;
+    if ((long long)d->N * Ho * Wo + 1024 > kMaxElems) return DSQ_ERR_UNSUPPORTED;
+    if (!aligned16(act_packed) || !aligned16(pix_code_sum) || !aligned16(w_packed) ||
+        !aligned16(w_aux) || !aligned16(out) || (acc_or_null && !aligned16(acc_or_null)))
+        return DSQ_ERR_ALIGN;
+
+    DsqConvArgs a;
+    a.N = d->N; a.C_in = d->C_in; a.H = d->H; a.W = d->W; a.C_out = d->C_out; a.R = d->R;
+    a.stride = d->stride; a.pad = d->pad; a.bits = d->bits;
+    a.Ho = Ho; a.Wo = Wo; a.Cp = Cp; a.Cop = Cop;
+    a.act = act_packed; a.pix_sum = pix_code_sum; a.l_a = l_a; a.u_a = u_a;
+    a.wq = w_packed;
+    a.delta_w = (const float *)w_aux;
+    a.l_w = a.delta_w + Cop;
+    a.sw_total = (const int32_t *)(a.l_w + Cop);
+    a.sw_tap = a.sw_total + Cop;
+    a.out = out; a.acc = acc_or_null; a.out_nchw = out_layout == DSQ_NCHW;
+
+    hipError_t e;
+    const bool patch_ok = dsq_conv_patch_supported(a);
+    if (g_conv_kernel == 2 && !patch_ok) return DSQ_ERR_UNSUPPORTED;
+    if (g_conv_kernel == 1 || !patch_ok) e = dsq_launch_conv_simple(a, (hipStream_t)hip_stream);
+    else e = dsq_launch_conv_patch(a, (hipStream_t)hip_stream);
+    return e == hipSuccess ? DSQ_OK : DSQ_ERR_HIP;
+}
+
+int dsq_set_conv_kernel(int which)
+{
+    int prev = g_conv_kernel;
+    if (which >= 0 && which <= 2) g_conv_kernel = which;
+    return prev;
+}
+
+const char *dsq_status_string(dsq_status s)
+{
+    switch (s) {
+    case DSQ_OK: return "ok";
+    case DSQ_ERR_NULL: return "a required pointer is NULL";
+    case DSQ_ERR_BITS: return "bits must be 2, 3 or 4";
+    case DSQ_ERR_RANGE: return "clip range must be finite with l < u";
+    case DSQ_ERR_SHAPE: return "invalid tensor or filter shape";
+    case DSQ_ERR_UNSUPPORTED: return "unsupported geometry, layout or tensor size";
+    case DSQ_ERR_ALIGN: return "device pointer is not 16-byte aligned";
+    case DSQ_ERR_SIZE: return "caller buffer is too small";
+    case DSQ_ERR_HIP: return "HIP runtime error at kernel launch";
+    }
+    return "unknown status";
+}
+
+}  // extern "C"

@@ -1,0 +1,38 @@
+// Internal launch interface between the C ABI (api.hip) and the kernels.
+// Arguments have already been validated by the caller.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#define DSQ_QUANT_MAX_PB 512   // most pixels one quantizer block may own
+
+struct DsqConvArgs {
+    int N, C_in, H, W, C_out, R, stride, pad, bits;
+    int Ho, Wo;
+    int Cp;        // C_in rounded up to 64
+    int Cop;       // C_out rounded up to 256
+    const void *act;          // packed activation codes
+    const int32_t *pix_sum;   // [N*H*W]
+    float l_a, u_a;
+    const void *wq;           // packed weights
+    const float *delta_w;     // [Cop]
+    const float *l_w;         // [Cop]
+    const int32_t *sw_total;  // [Cop]
+    const int32_t *sw_tap;    // [Cop][R*R]
+    float *out;
+    int32_t *acc;             // may be null
+    int out_nchw;
+};
+
+hipError_t dsq_launch_quantize_act(const float *x, int layout_nchw, int N, int C, int H, int W,
+                                   float l, float u, int bits, void *codes, int32_t *pix_sum,
+                                   hipStream_t stream);
+
+hipError_t dsq_launch_pack_weights(const float *w, const float *l_w, const float *u_w,
+                                   const uint8_t *codes, int C_out, int C_in, int R, int bits,
+                                   void *w_packed, void *w_aux, hipStream_t stream);
+
+hipError_t dsq_launch_conv_simple(const DsqConvArgs &a, hipStream_t stream);
+hipError_t dsq_launch_conv_patch(const DsqConvArgs &a, hipStream_t stream);
+// Whether the LDS-patch kernel supports this geometry.
+bool dsq_conv_patch_supported(const DsqConvArgs &a);

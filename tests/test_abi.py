@@ -1,0 +1,121 @@
+"""CPU-only checks of the C ABI: the library loads, exports every symbol the
+header declares, answers the size queries, and rejects bad arguments on the
+host before anything is launched (no GPU is touched)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_1908_05033_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "dsqconv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dsq_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    lib = B.load_library()
+    names = _declared_functions()
+    assert set(B.EXPORTS) == set(names)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_size_queries():
+    # 4-bit: C padded to 64, 2 codes per byte; 2-bit: 4 codes per byte
+    assert B.dsq_act_packed_bytes(32, 14, 14, 256, 4) == 32 * 14 * 14 * 128
+    assert B.dsq_act_packed_bytes(1, 2, 3, 24, 4) == 6 * 32
+    assert B.dsq_act_packed_bytes(1, 2, 3, 24, 3) == 6 * 32       # 3-bit in 4-bit containers
+    assert B.dsq_act_packed_bytes(1, 2, 3, 65, 2) == 6 * 32
+    assert B.dsq_wgt_packed_bytes(256, 256, 3, 3, 4) == 256 * 9 * 128
+    assert B.dsq_wgt_packed_bytes(24, 144, 1, 1, 4) == 256 * 96
+    assert B.dsq_wgt_aux_bytes(64, 3, 3) == 256 * (3 + 9) * 4
+    assert B.dsq_act_packed_bytes(0, 1, 1, 1, 4) == 0
+    assert B.dsq_act_packed_bytes(1, 1, 1, 1, 5) == 0
+
+
+def test_status_strings():
+    lib = B.load_library()
+    seen = set()
+    for s in range(9):
+        msg = lib.dsq_status_string(s).decode()
+        assert msg and msg not in seen
+        seen.add(msg)
+    assert lib.dsq_status_string(99).decode() == "unknown status"
+
+
+FAKE = 0x1000      # aligned, non-null; never dereferenced: validation fails first
+
+
+def _q(x=FAKE, layout=0, N=1, Cc=8, H=2, W=2, l=0.0, u=1.0, bits=4, codes=FAKE, nbytes=1 << 20,
+       pix=FAKE):
+    return B.load_library().dsq_quantize_act(x, layout, N, Cc, H, W, l, u, bits, codes, nbytes, pix, None)
+
+
+def test_quantize_act_rejects_bad_arguments():
+    assert _q(x=None) == 1
+    assert _q(codes=None) == 1
+    assert _q(pix=None) == 1
+    assert _q(bits=1) == 2 and _q(bits=5) == 2
+    assert _q(l=1.0, u=1.0) == 3 and _q(l=2.0, u=1.0) == 3
+    assert _q(l=float("nan")) == 3 and _q(u=float("inf")) == 3
+    assert _q(N=0) == 4 and _q(Cc=-1) == 4
+    assert _q(layout=7) == 5
+    assert _q(N=1 << 15, H=1 << 8, W=1 << 8, Cc=64, nbytes=1 << 62) == 5
+    assert _q(x=FAKE + 4) == 6 and _q(codes=FAKE + 8) == 6
+    assert _q(nbytes=2 * 2 * 32 - 1) == 7
+
+
+def _p(w=FAKE, lw=FAKE, uw=FAKE, codes=None, Co=8, Ci=8, R=3, S=3, bits=4, wp=FAKE, wb=1 << 24,
+       aux=FAKE, ab=1 << 20):
+    return B.load_library().dsq_pack_weights(w, lw, uw, codes, Co, Ci, R, S, bits, wp, wb, aux, ab, None)
+
+
+def test_pack_weights_rejects_bad_arguments():
+    assert _p(w=None, codes=None) == 1
+    assert _p(lw=None) == 1 and _p(wp=None) == 1 and _p(aux=None) == 1
+    assert _p(bits=8) == 2
+    assert _p(Co=0) == 4
+    assert _p(R=3, S=1) == 5 and _p(R=5, S=5) == 5 and _p(R=2, S=2) == 5
+    assert _p(wp=FAKE + 2) == 6
+    assert _p(wb=100) == 7 and _p(ab=100) == 7
+
+
+def _c(desc=None, act=FAKE, pix=FAKE, la=0.0, ua=1.0, wp=FAKE, aux=FAKE, out=FAKE, layout=0, acc=None,
+       **kw):
+    d = dict(N=1, C_in=8, H=4, W=4, C_out=8, R=3, S=3, stride=1, pad=1, bits=4)
+    d.update(kw)
+    desc = B.dsq_conv_desc(**d) if desc is None else desc
+    return B.load_library().dsq_conv2d(C.byref(desc), act, pix, la, ua, wp, aux, out, layout, acc, None)
+
+
+def test_conv2d_rejects_bad_arguments():
+    lib = B.load_library()
+    assert lib.dsq_conv2d(None, FAKE, FAKE, 0.0, 1.0, FAKE, FAKE, FAKE, 0, None, None) == 1
+    assert _c(act=None) == 1 and _c(out=None) == 1 and _c(aux=None) == 1
+    assert _c(bits=7) == 2
+    assert _c(la=1.0, ua=0.0) == 3
+    assert _c(N=0) == 4 and _c(H=1, W=1, pad=0) == 4
+    assert _c(R=3, S=1) == 5 and _c(R=5, S=5, pad=2) == 5
+    assert _c(stride=3) == 5 and _c(pad=3) == 5 and _c(R=1, S=1, pad=1) == 5
+    assert _c(layout=3) == 5
+    assert _c(N=64, H=1024, W=1024, C_in=64) == 5
+    assert _c(out=FAKE + 4) == 6 and _c(acc=FAKE + 4) == 6
+
+
+def test_binding_raises_on_error_status():
+    with pytest.raises(B.DsqError) as e:
+        B._check(2)
+    assert "bits" in str(e.value)
+
+
+def test_kernel_selector_roundtrip():
+    prev = B.dsq_set_conv_kernel(1)
+    assert B.dsq_set_conv_kernel(prev) == 1
+    assert B.dsq_set_conv_kernel(99) == prev      # out of range: unchanged
+    assert B.dsq_set_conv_kernel(prev) == prev
