@@ -1,0 +1,220 @@
+#!/usr/bin/env python3
+"""Benchmark of the b-bit quantized convolution hot path on one MI355X.
+
+A step is one pass of the per-batch hot path over one batch of synthetic
+input: dsq_quantize_act (fp32 activations -> packed codes + pixel sums)
+followed by dsq_conv2d (integer implicit GEMM + dequantizing epilogue -> fp32).
+dsq_pack_weights runs once per layer when a model is loaded; it is timed
+separately and is not part of the step.  The workload is the 3x3, 256->256,
+14x14, batch-32, 4-bit layer (the ResNet stage-3 shape).  Inputs live in HBM
+before the timed region; the steps rotate over enough buffer sets that the
+working set exceeds the 256 MB last-level cache.
+
+Prints ONE JSON line:  value = effective int-TOPS = 2*MACs*steps / time.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+INT8_MFMA_PEAK_TOPS = 5000.0     # MI355X dense int8 matrix peak
+HBM_PEAK_GBS = 8000.0
+
+# HBM bytes per conv launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
+# this workload (see profiles/), scaled by the copy-kernel factor; None until
+# measured.
+MEASURED_CONV_TRAFFIC_BYTES = None
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--config", type=int, default=2, help="BASELINE config (1 or 2)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sets", type=int, default=0, help="buffer sets to rotate over (0 = auto)")
+    return ap.parse_args()
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU only (the path shards over the batch "
+              "with no exchange; see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_1908_05033_amd import binding as B
+    from paper_1908_05033_amd import inputs
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    B.load_library()
+
+    layer, inp = inputs.make_config_layer(args.config)
+    L = layer
+    macs = L.macs
+
+    # ---- buffers: one weight set, `sets` activation/output sets ------------
+    in_bytes = L.N * L.C_in * L.H * L.W * 4
+    out_bytes = L.N * L.Ho * L.Wo * L.C_out * 4
+    code_bytes = B.dsq_act_packed_bytes(L.N, L.H, L.W, L.C_in, L.bits)
+    per_set = in_bytes + out_bytes + code_bytes + L.N * L.H * L.W * 4
+    sets = args.sets or max(2, int(np.ceil(600e6 / per_set)))
+    sets = min(sets, 256)
+
+    x_nhwc = inp["x"].permute(0, 2, 3, 1).contiguous()
+    bufs = []
+    for s in range(sets):
+        b = B.alloc_layer(L.N, L.C_in, L.H, L.W, L.C_out, L.R, L.S, L.stride, L.pad, L.bits)
+        b.x = x_nhwc.cuda() if s == 0 else bufs[0].x.clone()
+        bufs.append(b)
+    w = inp["w"].contiguous().cuda()
+    lw = torch.from_numpy(inp["l_w"]).cuda()
+    uw = torch.from_numpy(inp["u_w"]).cuda()
+    w_packed, w_aux = bufs[0].w_packed, bufs[0].w_aux
+    l_a, u_a = inp["l_a"], inp["u_a"]
+
+    stream = torch.cuda.Stream()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def pack():
+        B.dsq_pack_weights(w, lw, uw, None, L.C_out, L.C_in, L.R, L.S, L.bits, w_packed, w_aux)
+
+    def quant(b):
+        B.dsq_quantize_act(b.x, B.DSQ_NHWC, L.N, L.C_in, L.H, L.W, l_a, u_a, L.bits,
+                           b.act_packed, b.pix_code_sum)
+
+    def conv(b):
+        B.dsq_conv2d(b.desc, b.act_packed, b.pix_code_sum, l_a, u_a, w_packed, w_aux, b.out,
+                     B.DSQ_NHWC, None)
+
+    def capture(fn):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=stream):
+            for b in bufs:
+                fn(b)
+        return g
+
+    def timed_replays(g, n):
+        """n replays of a graph between two events on the launch stream."""
+        with torch.cuda.stream(stream):
+            torch.cuda.synchronize()
+            ev0.record(stream)
+            for _ in range(n):
+                g.replay()
+            ev1.record(stream)
+            torch.cuda.synchronize()
+        return ev0.elapsed_time(ev1) * 1e-3
+
+    with torch.cuda.stream(stream):
+        pack()
+        for b in bufs:
+            quant(b)
+            conv(b)
+        torch.cuda.synchronize()
+        # weight packing, timed on its own (model-load time, not part of a step)
+        ev0.record(stream)
+        for _ in range(10):
+            pack()
+        ev1.record(stream)
+        torch.cuda.synchronize()
+        pack_ms = ev0.elapsed_time(ev1) / 10
+
+    def step(b):
+        quant(b)
+        conv(b)
+
+    g_step, g_quant, g_conv = capture(step), capture(quant), capture(conv)
+
+    # ---- the timed region: exactly `steps` steps ---------------------------
+    n_warm = max(1, -(-args.warmup // sets))
+    n_rep = max(1, -(-args.steps // sets))
+    steps = n_rep * sets
+    warmup = n_warm * sets
+    timed_replays(g_step, n_warm)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    gpu_s = timed_replays(g_step, n_rep)
+    wall_s = time.perf_counter() - t0
+    step_s = max(gpu_s, 0.0) / steps
+    value = 2.0 * macs / step_s / 1e12
+
+    # ---- per-kernel average launch durations, same stream, HIP events ------
+    timed_replays(g_conv, n_warm)
+    conv_s = timed_replays(g_conv, n_rep) / steps
+    timed_replays(g_quant, n_warm)
+    quant_s = timed_replays(g_quant, n_rep) / steps
+
+    conv_tops = 2.0 * macs / conv_s / 1e12
+    quant_bytes = in_bytes + code_bytes + L.N * L.H * L.W * 4
+    result = {
+        "metric": "effective int-TOPS of b-bit conv2d (2*MACs/s), 1 GPU",
+        "value": round(value, 3),
+        "unit": "TOPS",
+        "n_gpus": 1,
+        "steps": steps,
+        "warmup": warmup,
+        "ms_per_step": round(step_s * 1e3, 6),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u%d codes, int8 MFMA, int32 accumulate, f64 epilogue -> f32" % L.bits,
+        "data": "synthetic",
+        "config": {
+            "workload": "config %d: %dx%d conv stride %d pad %d, N=%d, C_in=%d, C_out=%d, %dx%d, %d-bit "
+                        "acts and weights" % (args.config, L.R, L.S, L.stride, L.pad, L.N, L.C_in, L.C_out,
+                                              L.H, L.W, L.bits),
+            "step": "dsq_quantize_act + dsq_conv2d (weights packed once, outside the step)",
+            "gemm_MxNxK": [L.N * L.Ho * L.Wo, L.C_out, L.C_in * L.R * L.S],
+            "macs_per_step": macs,
+            "buffer_sets": sets,
+            "launch": "hipGraph of %d steps replayed %d times" % (sets, n_rep),
+        },
+        "kernels": {
+            "dsq_conv2d_us": round(conv_s * 1e6, 3),
+            "dsq_conv2d_TOPS": round(conv_tops, 2),
+            "dsq_quantize_act_us": round(quant_s * 1e6, 3),
+            "dsq_quantize_act_GBps": round(quant_bytes / quant_s / 1e9, 1),
+            "dsq_pack_weights_us_not_in_step": round(pack_ms * 1e3, 2),
+            "host_wall_s_timed_region": round(wall_s, 4),
+        },
+        "roofline": {
+            "kernel": "dsq_conv2d",
+            "bound": "mfma",
+            "achieved": round(conv_tops, 2),
+            "peak": INT8_MFMA_PEAK_TOPS,
+            "unit": "TOP/s",
+            "frac": round(conv_tops / INT8_MFMA_PEAK_TOPS, 4),
+            "traffic": MEASURED_CONV_TRAFFIC_BYTES,
+        },
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        xs = inp["x"].numpy()
+        ws = inp["w"].numpy()
+        t0 = time.perf_counter()
+        a_code = oracle.quantize(xs, l_a, u_a, L.bits)
+        w_code = oracle.quantize_weights(ws, inp["l_w"], inp["u_w"], L.bits)
+        oracle.conv_real(a_code, l_a, u_a, w_code, inp["l_w"], inp["u_w"], L.bits, L.stride, L.pad)
+        cpu_s = time.perf_counter() - t0
+        result["cpu_baseline"] = {
+            "value": round(2.0 * macs / cpu_s / 1e12, 6),
+            "unit": "TOPS",
+            "cores": oracle.threads(),
+            "kind": "oracle",
+            "sample": "one full batch of the same workload (quantize + direct conv on dequantized "
+                      "doubles), %.2f s" % cpu_s,
+        }
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

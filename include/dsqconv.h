@@ -17,8 +17,8 @@
  *
  * Conventions for every call
  *   - All tensor pointers are DEVICE memory owned by the caller; scalars and
- *     the descriptor struct are host values.  The library allocates nothing,
- *     keeps no state and never synchronises: work is enqueued on `hip_stream`
+ *     the descriptor struct are host values.  The library allocates nothing
+ *     and never synchronises: work is enqueued on `hip_stream`
  *     (a hipStream_t passed as void*, NULL = default stream) and the call
  *     returns at once.
  *   - Arguments are validated on the host before anything is launched; on any
@@ -151,8 +151,13 @@ dsq_status dsq_conv2d(const dsq_conv_desc *d, const void *act_packed,
                       void *hip_stream);
 
 /* Selects the convolution kernel: 0 = automatic (default), 1 = the simple
- * one-wave-per-tile kernel, 2 = the LDS-patch kernel.  For tests and
- * benchmarking; process-wide, not thread-safe.  Returns the previous value. */
+ * one-wave-per-tile kernel, 2 = the LDS-patch kernel with its tile chosen by
+ * problem size, 3 / 4 / 5 = the LDS-patch kernel with the 112x64 / 224x128 /
+ * 224x64 (pixels x channels) tile.  With 2..5, dsq_conv2d returns
+ * DSQ_ERR_UNSUPPORTED instead of falling back when the patch kernel cannot
+ * take the geometry.  For tests and benchmarking; this selector is the only
+ * state the library keeps; process-wide, not thread-safe.  Returns the
+ * previous value; values outside 0..5 change nothing. */
 int dsq_set_conv_kernel(int which);
 
 /* Static, NUL-terminated description of a status code. */

@@ -8,7 +8,7 @@
 
 namespace {
 
-int g_conv_kernel = 0;   // 0 auto, 1 simple, 2 patch
+int g_conv_kernel = 0;   // 0 auto, 1 simple, 2 patch (auto tile), 3..5 patch with a fixed tile
 
 bool bits_ok(int bits) { return bits >= 2 && bits <= 4; }
 bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
@@ -114,17 +114,18 @@ dsq_status dsq_conv2d(const dsq_conv_desc *d, const void *act_packed, const int3
     a.out = out; a.acc = acc_or_null; a.out_nchw = out_layout == DSQ_NCHW;
 
     hipError_t e;
-    const bool patch_ok = dsq_conv_patch_supported(a);
-    if (g_conv_kernel == 2 && !patch_ok) return DSQ_ERR_UNSUPPORTED;
-    if (g_conv_kernel == 1 || !patch_ok) e = dsq_launch_conv_simple(a, (hipStream_t)hip_stream);
-    else e = dsq_launch_conv_patch(a, (hipStream_t)hip_stream);
+    const int force_tile = g_conv_kernel >= 3 ? g_conv_kernel - 3 : -1;
+    const bool patch_ok = g_conv_kernel != 1 && dsq_conv_patch_supported(a, force_tile);
+    if (g_conv_kernel >= 2 && !patch_ok) return DSQ_ERR_UNSUPPORTED;
+    if (!patch_ok) e = dsq_launch_conv_simple(a, (hipStream_t)hip_stream);
+    else e = dsq_launch_conv_patch(a, force_tile, (hipStream_t)hip_stream);
     return e == hipSuccess ? DSQ_OK : DSQ_ERR_HIP;
 }
 
 int dsq_set_conv_kernel(int which)
 {
     int prev = g_conv_kernel;
-    if (which >= 0 && which <= 2) g_conv_kernel = which;
+    if (which >= 0 && which <= 5) g_conv_kernel = which;
     return prev;
 }
 

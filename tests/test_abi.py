@@ -118,4 +118,5 @@ def test_kernel_selector_roundtrip():
     prev = B.dsq_set_conv_kernel(1)
     assert B.dsq_set_conv_kernel(prev) == 1
     assert B.dsq_set_conv_kernel(99) == prev      # out of range: unchanged
+    assert B.dsq_set_conv_kernel(-1) == prev
     assert B.dsq_set_conv_kernel(prev) == prev

@@ -11,14 +11,14 @@ from paper_1908_05033_amd import inputs
 
 pytestmark = pytest.mark.gpu
 
-KERNELS = [1, 2]       # 1 = simple, 2 = LDS-patch (skipped where unsupported)
+KERNELS = [1, 3, 4, 5]   # 1 = simple; 3/4/5 = LDS-patch kernel with each of its tiles
 
 
 def _run(layer, inp, kernel, **kw):
     try:
         return run_layer_gpu(layer, inp, kernel=kernel, **kw)
     except B.DsqError as e:
-        if kernel == 2 and e.status == 5:
+        if kernel >= 2 and e.status == 5:
             pytest.skip("geometry not supported by the patch kernel")
         raise
 
