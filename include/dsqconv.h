@@ -44,11 +44,13 @@
  *   consecutive channels as four int8.
  *   Activations: [N][H][W][Cp] with Cp = C rounded up to a multiple of 64,
  *   channels >= C hold code 0; one pixel is Cp*container/8 bytes.
- *   Weights: blocks of 16 output channels x 64 input channels of one filter
- *   tap, ordered [Cop/16][Cp/64][R*S][64 lanes], lane = 16*g + (o % 16)
- *   holding channels 64*cb + 16*g + 0..15 of output channel o (2 words at
- *   4-bit, 1 word at 2-bit).  Cop = C_out rounded up to a multiple of 256;
- *   rows >= C_out and channels >= C_in hold code 0.
+ *   Weights: blocks of 32 output channels x 64 input channels of one filter
+ *   tap, ordered [Cop/32][Cp/64][R*S][64 lanes][2 K halves]; lane = 32*h +
+ *   (o % 32), and K half kh of that lane holds channels
+ *   64*cb + 32*kh + 16*h + 0..15 of output channel o (2 words at 4-bit, 1 word
+ *   at 2-bit) -- the operand order of the 32x32x32 int8 matrix instruction.
+ *   Cop = C_out rounded up to a multiple of 256; rows >= C_out and channels
+ *   >= C_in hold code 0.
  */
 #ifndef DSQCONV_H
 #define DSQCONV_H
@@ -152,8 +154,8 @@ dsq_status dsq_conv2d(const dsq_conv_desc *d, const void *act_packed,
 
 /* Selects the convolution kernel: 0 = automatic (default), 1 = the simple
  * one-wave-per-tile kernel, 2 = the LDS-patch kernel with its tile chosen by
- * problem size, 3 / 4 / 5 = the LDS-patch kernel with the 112x64 / 224x128 /
- * 224x64 (pixels x channels) tile.  With 2..5, dsq_conv2d returns
+ * problem size, 3 / 4 / 5 = the LDS-patch kernel with the 128x64 / 128x128 /
+ * 256x128 (pixels x channels) tile.  With 2..5, dsq_conv2d returns
  * DSQ_ERR_UNSUPPORTED instead of falling back when the patch kernel cannot
  * take the geometry.  For tests and benchmarking; this selector is the only
  * state the library keeps; process-wide, not thread-safe.  Returns the

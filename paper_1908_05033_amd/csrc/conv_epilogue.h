@@ -7,7 +7,9 @@
 // with ACC = sum ca*cw (the integer GEMM), SA = sum ca, SW = sum cw and KV the
 // number of (tap, channel) pairs, all over in-image taps only.  The four terms
 // are combined in binary64 (terms 1 and 3 nearly cancel for symmetric weight
-// ranges) and rounded once to binary32.
+// ranges) and the sum is rounded once to binary32.  Every kernel evaluates
+//   fma(Da*Dw, ACC, (Da*l_w)*SA)  [+ (l_a*Dw)*SW + KV*(l_a*l_w)]
+// in this order, so all store paths give identical bits.
 #pragma once
 #include "dsq_device.h"
 #include "dsq_kernels.h"
@@ -61,7 +63,7 @@ __device__ __forceinline__ void dsq_store4(const DsqConvArgs &a, const DsqPixel 
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const double da = (double)delta_a, dwj = (double)dwv[j], lwj = (double)lwv[j];
-        double v = (da * dwj) * (double)accv[j] + (lwj * da) * (double)p.sa;
+        double v = __builtin_fma(da * dwj, (double)accv[j], (da * lwj) * (double)p.sa);
         if (a.l_a != 0.0f) {
             int sw;
             if (full) sw = a.sw_total[o0 + j];

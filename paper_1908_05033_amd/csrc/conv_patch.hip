@@ -2,252 +2,463 @@
 //
 // GEMM view of Algorithm 1 step 5 of the paper: rows = output channels,
 // columns = output pixels, K = filter taps x input channels, run on
-// v_mfma_i32_16x16x64_i8 with int32 accumulation (the integer-arithmetic
-// deployment of Sec. 3.5 / 4.5, re-designed for the matrix cores).
+// v_mfma_i32_32x32x32_i8 with int32 accumulation (the integer-arithmetic
+// deployment of Sec. 3.5 / 4.5, re-designed for the matrix cores; the
+// 16x16x64 form of the instruction issues at half the rate on this chip).
 //
-// A workgroup (4 wavefronts) owns a tile of TR output rows x TW output columns
-// (TR*TW <= 16*FRAGS pixels; rows are counted through the whole batch, so a
-// tile may span images) and BC = 16*CT*WC output channels.  K is walked in
-// stages of 64 input channels.  For a stage, the input patch that all R*R taps
-// of the tile touch is read from HBM/L2 once, unpacked from 2/4-bit codes to
-// int8 and kept in LDS; the taps then read shifted windows of it, so the
-// R*R-fold re-use of the activations never leaves the CU.  Positions of the
-// patch that fall in the zero padding hold code 0: they add nothing to the
-// integer sums, and the epilogue's SA/SW/KV terms leave them out as well.
-// Weight fragments were laid out per lane by dsq_pack_weights and go from
-// global memory straight to registers, one stage ahead.  The patch of the
-// next stage is fetched while the current one is multiplied (two LDS buffers,
-// one barrier per stage).
+// A workgroup (4 wavefronts, WP x WC) owns BP = 32*PF*WP consecutive output
+// pixels of a strip of TW output columns (pixels are numbered row by row
+// through the whole batch, so a tile may span rows and images) and
+// BC = 32*CT*WC output channels; a wavefront owns PF fragments of 32 pixels and
+// CT tiles of 32 channels.  K is walked in stages of 64 input channels.  For a
+// stage, the input patch that all R*R taps of the tile touch is read from
+// HBM/L2 once, unpacked from 2/4-bit codes to int8 and kept in LDS; the taps
+// then read shifted windows of it, so the R*R-fold re-use of the activations
+// never leaves the CU.  Positions of the patch that fall in the zero padding
+// hold code 0: they add nothing to the integer sums, and the epilogue's SA /
+// SW / KV terms leave them out as well.  Weight fragments were laid out per
+// lane by dsq_pack_weights and go from global memory straight to registers,
+// each refilled for the next stage right after its use.  The patch of the next
+// stage is fetched while the current one is multiplied (two LDS buffers, one
+// barrier per stage).
 //
-// LDS layout of a patch: pixel (prow, pcol) at prow*RP + pcol*80 bytes, 64
-// bytes of int8 + 16 bytes of padding, so that the 16 pixels of a fragment
-// (consecutive tile pixels) start in 16 different 16-byte bank groups; RP adds
-// a per-row skew that keeps this true when a fragment wraps to the next row.
+// Feed rates that shape the tiles (measured on MI355X): LDS delivers 128 B/clk
+// per CU, the vector L1 one wave-wide load (<= 16 B per lane) per 16 clk per
+// CU.  With 4 waves issuing MFMAs back to back, activation fragments keep the
+// LDS busy 1/CT of the time and weight fragments keep the L1 busy 1/PF of the
+// time.
+#include <type_traits>
+
 #include "conv_epilogue.h"
 
 namespace {
 
 constexpr int PIX_STRIDE = 80;   // LDS bytes per patch pixel (64 used)
 
+#ifdef DSQ_TRACE
+// Developer build only: per-wave phase timestamps (s_memtime ticks).
+__device__ unsigned long long dsq_trace_buf[4096 * 16];
+#define DSQ_STAMP(slot)                                                              \
+    do {                                                                             \
+        if (lane == 0 && blockIdx.y == 0 && blockIdx.x < 1024 && (slot) < 16)        \
+            dsq_trace_buf[(blockIdx.x * 4 + wave) * 16 + (slot)] = __builtin_amdgcn_s_memtime(); \
+    } while (0)
+#else
+#define DSQ_STAMP(slot) do { } while (0)
+#endif
+
 struct PatchPlan {
-    int TR, TW;        // tile: output rows x output columns
-    int tiles_w;       // column tiles per output row
-    int row_tiles;     // ceil(N*Ho / TR)
+    int TW;            // strip width in output columns
+    int BP;            // pixels per tile
+    int tiles_w;       // strips per output row
+    int row_tiles;     // tiles per strip
     int PR, PC;        // patch rows (max over tiles) x patch columns
     int RP;            // LDS bytes per patch row
-    int buf_bytes;     // LDS bytes of one patch buffer
+    int buf_bytes;     // LDS bytes of one patch buffer (incl. a 64-byte dump slot at its end)
     int Hp;            // H + 2*pad: rows of one image in the padded row space
     int units;         // 16-byte fetch units per stage
+    int aux_off;       // LDS offset of the small tables that follow the patch / staging area
+    int step_q, step_r;   // (256 / units-per-pixel) divided by PC: quotient and remainder
+    float inv_PC, inv_TW, inv_Hp, inv_Ho, inv_tiles_w;   // reciprocals for the index divisions
 };
 
-template <int CONT, int R, int FRAGS, int WP, int WC, int CT, int UPT>
+// x / d for 0 <= x < 2^22 and d >= 1, with a float reciprocal and a fix-up.
+__device__ __forceinline__ int fdiv(int x, int d, float inv_d, int &rem)
+{
+    int q = (int)((float)x * inv_d);
+    int r = x - q * d;
+    if (r < 0) { --q; r += d; }
+    if (r >= d) { ++q; r -= d; }
+    rem = r;
+    return q;
+}
+
+// Epilogue for the cases the kernel's inline fast path does not cover; kept out
+// of line so that its address arithmetic does not weigh on the main kernel.
+__device__ __noinline__ void store4_general(const DsqConvArgs &a, int m, int o0, v4i acc, float delta_a)
+{
+    const DsqPixel px = dsq_pixel_info(a, m, a.N * a.Ho * a.Wo);
+    dsq_store4(a, px, m, o0, acc, delta_a);
+}
+
+template <int CONT, int R, int WP, int WC, int PF, int CT, int UPT>
 __global__ __launch_bounds__(256) void conv_patch_kernel(DsqConvArgs a, PatchPlan pl)
 {
     constexpr int T = R * R;
-    constexpr int WPL = CONT == 4 ? 2 : 1;        // packed weight words per lane per K64 block
     constexpr int UPP = CONT == 4 ? 2 : 1;        // 16-byte fetch units per patch pixel
     constexpr int KB_BYTES = 64 * CONT / 8;       // packed bytes of 64 channels
-    constexpr int PF = (FRAGS + WP - 1) / WP;     // pixel fragments per wave (max)
+    constexpr int WLANE = 4 * CONT;               // packed weight bytes per lane per (tile, cb, tap)
     static_assert(WP * WC == 4, "four waves per workgroup");
+    static_assert(64 * CT * WC <= 256, "one thread per staged channel constant");
+    typedef typename std::conditional<CONT == 4, v4i, v2i>::type wpack_t;
 
     extern __shared__ __attribute__((aligned(16))) char lds[];
+    // LDS: [patch buffer 0][patch buffer 1] (re-used by the epilogue as staging)
+    //      at aux_off: [double Da*Dw[BC]][double Da*l_w[BC]]
+    //                  [int pixel code sums of the patch, PR*PC]
+    constexpr int BC = 32 * CT * WC;
+    double *pq_lds = reinterpret_cast<double *>(lds + pl.aux_off);
+    int *pix_lds = reinterpret_cast<int *>(pq_lds + 2 * BC);
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int col = lane & 15, g = lane >> 4;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int col = lane & 31, h = lane >> 5;
     const int wp = wave % WP, wc = wave / WP;
+    DSQ_STAMP(0);
 
-    const int tile_w = blockIdx.x % pl.tiles_w;
-    const int tile_r = blockIdx.x / pl.tiles_w;
-    const int NHo = a.N * a.Ho;
-    const int gr0 = tile_r * pl.TR;             // first output row (batch-wide numbering)
-    const int ow0 = tile_w * pl.TW;
-    const int n0 = gr0 / a.Ho;
-    const int v0 = n0 * pl.Hp + (gr0 - n0 * a.Ho) * a.stride;   // first padded input row
-    const int vc0 = ow0 * a.stride;                              // first padded input column
+    // The kernel arguments live in memory that is slow to reach; touching all of
+    // them here makes the compiler fetch them in one batch instead of one
+    // round trip per group of first uses.  (The test cannot be true: N >= 1.)
+    {
+        const long long touch =
+            (long long)a.N + a.C_in + a.H + a.W + a.C_out + a.stride + a.pad + a.bits + a.Ho + a.Wo + a.Cp +
+            (long long)(a.out_nchw & 1) + (long long)(intptr_t)a.act + (long long)(intptr_t)a.pix_sum +
+            (long long)(intptr_t)a.wq + (long long)(intptr_t)a.delta_w + (long long)(intptr_t)a.l_w +
+            (long long)(intptr_t)a.out + (long long)(intptr_t)a.acc + (long long)(intptr_t)a.sw_total +
+            (long long)(intptr_t)a.sw_tap + a.R + a.Cop + pl.TW + pl.BP + pl.tiles_w + pl.PR + pl.PC +
+            pl.RP + pl.buf_bytes + pl.Hp + pl.units + pl.aux_off + pl.step_q + pl.step_r +
+            (long long)__float_as_int(pl.inv_PC) + __float_as_int(pl.inv_TW) + __float_as_int(pl.inv_Hp) +
+            __float_as_int(pl.inv_Ho) + __float_as_int(pl.inv_tiles_w) + __float_as_int(a.l_a) + __float_as_int(a.u_a);
+        if (a.N == 0 && touch == 0x7FFFFFFFFFFFFFFFLL) return;
+    }
+
     const int NCB = a.Cp / 64;
-    const size_t row_bytes = (size_t)a.Cp * CONT / 8;
-    const char *act = (const char *)a.act;
+    const int NHo = a.N * a.Ho;
 
-    // ---- per-thread fetch units of the patch -------------------------------
-    int src_off[UPT];      // byte offset into act of the unit at channel block 0, or -1
-    int dst_off[UPT];      // LDS byte offset inside a patch buffer, or -1 (no such unit)
-#pragma unroll
-    for (int k = 0; k < UPT; ++k) {
-        const int u = tid + 256 * k;
-        src_off[k] = -1;
-        dst_off[k] = -1;
-        if (u < pl.units) {
-            const int pp = u / UPP, half = u - pp * UPP;
-            const int prow = pp / pl.PC, pcol = pp - prow * pl.PC;
-            dst_off[k] = prow * pl.RP + pcol * PIX_STRIDE + half * 32;
-            const int v = v0 + prow;
-            const int n = v / pl.Hp;
-            const int ih = v - n * pl.Hp - a.pad;
-            const int iw = vc0 + pcol - a.pad;
-            if (n < a.N && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W)
-                src_off[k] = (int)((((size_t)n * a.H + ih) * a.W + iw) * row_bytes) + half * 16;
-        }
-    }
-
-    // ---- per-lane LDS offsets of the fragments' pixels ---------------------
-    int frag_off[PF];
-    int frag_gr[PF], frag_ow[PF];     // output row / column of this lane's pixel, -1 if none
-#pragma unroll
-    for (int f = 0; f < PF; ++f) {
-        const int fi = wp + WP * f;                 // fragment index inside the tile
-        const int t = fi * 16 + col;
-        int tr = t / pl.TW, tc = t - tr * pl.TW;
-        const int gr = gr0 + tr, ow = ow0 + tc;
-        const bool ok = fi < FRAGS && tr < pl.TR && gr < NHo && ow < a.Wo;
-        frag_gr[f] = ok ? gr : -1;
-        frag_ow[f] = ow;
-        int prow = 0, pcol = 0;
-        if (ok) {
-            const int n = gr / a.Ho;
-            prow = n * pl.Hp + (gr - n * a.Ho) * a.stride - v0;
-            pcol = tc * a.stride;
-        }
-        frag_off[f] = prow * pl.RP + pcol * PIX_STRIDE + 16 * g;
-    }
-
-    // ---- weights: lane-ordered fragments, [ct][cb][tap][lane][WPL] ---------
+    // ---- weights first: their addresses need only the lane and block ids ----
+    // lane-ordered fragments, [ct][cb][tap][lane][both K halves]
     const int ct0 = (blockIdx.y * WC + wc) * CT;
-    const uint32_t *wq = (const uint32_t *)a.wq;
-    auto wptr = [&](int c, int cb) {
-        return wq + ((((size_t)(ct0 + c) * NCB + cb) * T) * 64 + lane) * WPL;
-    };
-
-    v4i acc[PF][CT];
-#pragma unroll
-    for (int f = 0; f < PF; ++f)
-#pragma unroll
-        for (int c = 0; c < CT; ++c) acc[f][c] = (v4i){0, 0, 0, 0};
-
-    v4i pre[UPT];                 // packed patch units in flight
-    uint32_t wreg[CT][T][WPL];    // packed weight fragments of the current stage; each is
-                                  // refilled for the next stage as soon as it has been used
-
-    auto fetch_patch = [&](int cb) {
-#pragma unroll
-        for (int k = 0; k < UPT; ++k) {
-            pre[k] = (v4i){0, 0, 0, 0};
-            if (src_off[k] >= 0)
-                pre[k] = *reinterpret_cast<const v4i *>(act + (size_t)(uint32_t)src_off[k] + (size_t)cb * KB_BYTES);
-        }
-    };
+    const uint32_t lane_woff = (uint32_t)lane * WLANE;
+    wpack_t wreg[CT][T];     // packed weight fragments of the current stage; each is
+                             // refilled for the next stage as soon as it has been used
     auto fetch_weight = [&](int c, int t, int cb) {
-        const uint32_t *p = wptr(c, cb) + (size_t)t * 64 * WPL;
-        if (WPL == 2) {
-            v2i w2 = *reinterpret_cast<const v2i *>(p);
-            wreg[c][t][0] = (uint32_t)w2.x;
-            wreg[c][t][WPL - 1] = (uint32_t)w2.y;
-        } else {
-            wreg[c][t][0] = p[0];
-        }
+        const char *p = (const char *)a.wq +
+                        ((((size_t)(ct0 + c) * NCB + cb) * T + t) * 64) * WLANE + lane_woff;
+        wreg[c][t] = *reinterpret_cast<const wpack_t *>(p);
     };
-    auto store_patch = [&](char *buf) {
-#pragma unroll
-        for (int k = 0; k < UPT; ++k) {
-            if (dst_off[k] < 0) continue;
-            char *d = buf + dst_off[k];
-            if (CONT == 4) {
-                // 16 packed bytes = 32 channels -> 32 int8
-                *reinterpret_cast<v4i *>(d) = dsq_unpack16_c4((v2i){pre[k].x, pre[k].y});
-                *reinterpret_cast<v4i *>(d + 16) = dsq_unpack16_c4((v2i){pre[k].z, pre[k].w});
-            } else {
-                // 16 packed bytes = 64 channels -> 64 int8
-                *reinterpret_cast<v4i *>(d) = dsq_unpack2((uint32_t)pre[k].x);
-                *reinterpret_cast<v4i *>(d + 16) = dsq_unpack2((uint32_t)pre[k].y);
-                *reinterpret_cast<v4i *>(d + 32) = dsq_unpack2((uint32_t)pre[k].z);
-                *reinterpret_cast<v4i *>(d + 48) = dsq_unpack2((uint32_t)pre[k].w);
-            }
-        }
-    };
-    // One stage: all taps of 64 input channels.  next_cb < 0: last stage.
-    auto compute = [&](const char *buf, int next_cb, char *nextbuf) {
-#pragma unroll
-        for (int t = 0; t < T; ++t) {
-            const int tap_off = (t / R) * pl.RP + (t % R) * PIX_STRIDE;
-            v4i af[PF];
-#pragma unroll
-            for (int f = 0; f < PF; ++f)
-                af[f] = *reinterpret_cast<const v4i *>(buf + frag_off[f] + tap_off);
-#pragma unroll
-            for (int c = 0; c < CT; ++c) {
-                v4i wf;
-                if (CONT == 4) wf = dsq_unpack16_c4((v2i){(int)wreg[c][t][0], (int)wreg[c][t][WPL - 1]});
-                else wf = dsq_unpack2(wreg[c][t][0]);
-                if (next_cb >= 0) fetch_weight(c, t, next_cb);
-#pragma unroll
-                for (int f = 0; f < PF; ++f)
-                    if (wp + WP * f < FRAGS)
-                        acc[f][c] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf, af[f], acc[f][c], 0, 0, 0);
-            }
-            // half way through the taps the next stage's patch has arrived:
-            // unpack it into the other buffer while the matrix cores are busy
-            if (next_cb >= 0 && t == T / 2) store_patch(nextbuf);
-        }
-    };
-
-    fetch_patch(0);
 #pragma unroll
     for (int c = 0; c < CT; ++c)
 #pragma unroll
         for (int t = 0; t < T; ++t) fetch_weight(c, t, 0);
-    store_patch(lds);
-    __syncthreads();
 
-    for (int cb = 0; cb < NCB; ++cb) {
-        const bool more = cb + 1 < NCB;
-        char *cur = lds + (cb & 1) * pl.buf_bytes;
-        char *nxt = lds + ((cb + 1) & 1) * pl.buf_bytes;
-        if (more) fetch_patch(cb + 1);
-        compute(cur, more ? cb + 1 : -1, nxt);
-        __syncthreads();
+    DSQ_STAMP(10);
+    // per-channel dequantization constants of this workgroup's channels -> LDS
+    float chan_const = 0.f;
+    if (tid < 2 * BC) {
+        const int o = blockIdx.y * BC + (tid < BC ? tid : tid - BC);      // < Cop by construction
+        chan_const = tid < BC ? a.delta_w[o] : a.l_w[o];
     }
 
-    // ---- epilogue -----------------------------------------------------------
-    const int top = (1 << a.bits) - 1;
-    const float delta_a = dsq_delta(a.l_a, a.u_a, top);
-    const int M = NHo * a.Wo;
+    // ---- tile position -------------------------------------------------------
+    int tile_w;
+    const int tile_r = fdiv((int)blockIdx.x, pl.tiles_w, pl.inv_tiles_w, tile_w);
+    const int t0 = tile_r * pl.BP;              // first pixel of the tile, numbered inside the strip
+    const int ow0 = tile_w * pl.TW;
+    int tc0;
+    const int gr0 = fdiv(t0, pl.TW, pl.inv_TW, tc0);   // its output row (batch-wide numbering)
+    int oh0;
+    const int n0 = fdiv(gr0, a.Ho, pl.inv_Ho, oh0);
+    const int v0 = n0 * pl.Hp + oh0 * a.stride;   // first padded input row of the patch
+    const int vc0 = ow0 * a.stride;               // first padded input column of the patch
+    const uint32_t row_bytes = (uint32_t)a.Cp * CONT / 8;
+
+    // ---- per-thread fetch units of the patch ---------------------------------
+    // unit u = tid + 256*k covers half `u % UPP` of patch pixel u / UPP
+    uint32_t src_off[UPT];   // byte offset into act of the unit at channel block 0
+    int dst_off[UPT];        // LDS byte offset inside a patch buffer (dump slot if no such unit)
+    int pix_val[UPT];        // code sum of the unit's pixel (first half-unit only)
+    uint32_t src_valid = 0;  // bit k: unit k reads real data (else: zero padding)
+    const int dump_off = pl.buf_bytes - 64;
+    {
+        const int half = UPP == 2 ? (tid & 1) : 0;
+        int pcol;
+        int prow = fdiv(UPP == 2 ? (tid >> 1) : tid, pl.PC, pl.inv_PC, pcol);
+#pragma unroll
+        for (int k = 0; k < UPT; ++k) {
+            src_off[k] = 0;
+            dst_off[k] = dump_off;
+            pix_val[k] = 0;
+            if (prow < pl.PR) {
+                dst_off[k] = prow * pl.RP + pcol * PIX_STRIDE + half * 32;
+                int ihp;
+                const int n = fdiv(v0 + prow, pl.Hp, pl.inv_Hp, ihp);
+                const int ih = ihp - a.pad;
+                const int iw = vc0 + pcol - a.pad;
+                if (n < a.N && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W) {
+                    const uint32_t pix = (uint32_t)((n * a.H + ih) * a.W + iw);
+                    src_off[k] = pix * row_bytes + half * 16;
+                    src_valid |= 1u << k;
+                    if (half == 0) pix_val[k] = a.pix_sum[pix];
+                }
+            }
+            prow += pl.step_q;
+            pcol += pl.step_r;
+            if (pcol >= pl.PC) { pcol -= pl.PC; ++prow; }
+        }
+    }
+
+    v4i pre[UPT];            // packed patch units in flight
+    auto fetch_patch = [&](int cb) {
+        const char *base = (const char *)a.act + (size_t)cb * KB_BYTES;
+#pragma unroll
+        for (int k = 0; k < UPT; ++k) pre[k] = *reinterpret_cast<const v4i *>(base + src_off[k]);
+    };
+    auto store_patch = [&](char *buf) {
+#pragma unroll
+        for (int k = 0; k < UPT; ++k) {
+            const v4i pk = (src_valid >> k & 1) ? pre[k] : (v4i){0, 0, 0, 0};
+            char *d = buf + dst_off[k];
+            if (CONT == 4) {
+                // 16 packed bytes = 32 channels -> 32 int8
+                *reinterpret_cast<v4i *>(d) = dsq_unpack16_c4((v2i){pk.x, pk.y});
+                *reinterpret_cast<v4i *>(d + 16) = dsq_unpack16_c4((v2i){pk.z, pk.w});
+            } else {
+                // 16 packed bytes = 64 channels -> 64 int8
+                *reinterpret_cast<v4i *>(d) = dsq_unpack2((uint32_t)pk.x);
+                *reinterpret_cast<v4i *>(d + 16) = dsq_unpack2((uint32_t)pk.y);
+                *reinterpret_cast<v4i *>(d + 32) = dsq_unpack2((uint32_t)pk.z);
+                *reinterpret_cast<v4i *>(d + 48) = dsq_unpack2((uint32_t)pk.w);
+            }
+        }
+    };
+    fetch_patch(0);
+    DSQ_STAMP(13);
+
+    // ---- per-lane LDS offsets of the fragments' pixels -----------------------
+    // Tile pixels past the end of the strip multiply patch pixel 0 and are
+    // never stored.
+    int frag_off[PF];       // byte offset of the pixel's first tap inside a patch buffer
+    int frag_pp[PF];        // index of that patch pixel (prow*PC + pcol)
+    int frag_m[PF];         // output pixel index n*Ho*Wo + oy*Wo + ox, or -1
 #pragma unroll
     for (int f = 0; f < PF; ++f) {
-        if (wp + WP * f >= FRAGS) continue;
-        const int m = frag_gr[f] >= 0 ? frag_gr[f] * a.Wo + frag_ow[f] : M;
-        const DsqPixel px = dsq_pixel_info(a, m, M);
-#pragma unroll
-        for (int c = 0; c < CT; ++c)
-            dsq_store4(a, px, m, (ct0 + c) * 16 + 4 * g, acc[f][c], delta_a);
+        const int t = t0 + (wp * PF + f) * 32 + col;
+        int tc;
+        const int gr = fdiv(t, pl.TW, pl.inv_TW, tc);
+        const int ow = ow0 + tc;
+        const bool ok = gr < NHo && ow < a.Wo;
+        int prow = 0, pcol = 0;
+        if (ok) {
+            int oh;
+            const int n = fdiv(gr, a.Ho, pl.inv_Ho, oh);
+            prow = n * pl.Hp + oh * a.stride - v0;
+            pcol = tc * a.stride;
+        }
+        frag_m[f] = ok ? gr * a.Wo + ow : -1;
+        frag_pp[f] = prow * pl.PC + pcol;
+        frag_off[f] = prow * pl.RP + pcol * PIX_STRIDE + 16 * h;
     }
+
+    v16i acc[PF][CT];
+    const v16i zero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+    for (int f = 0; f < PF; ++f)
+#pragma unroll
+        for (int c = 0; c < CT; ++c) acc[f][c] = zero16;
+
+    // One stage: all taps of 64 input channels.  HAS_NEXT: the weights and the
+    // patch of stage next_cb are fetched / stored on the way.
+    auto compute = [&](auto has_next, const char *buf, int next_cb, char *nextbuf) {
+        constexpr bool HAS_NEXT = decltype(has_next)::value;
+        v4i af[2][PF][2];
+#pragma unroll
+        for (int f = 0; f < PF; ++f)
+#pragma unroll
+            for (int kh = 0; kh < 2; ++kh)
+                af[0][f][kh] = *reinterpret_cast<const v4i *>(buf + frag_off[f] + 32 * kh);
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            if (t + 1 < T) {
+                const int tap_off = ((t + 1) / R) * pl.RP + ((t + 1) % R) * PIX_STRIDE;
+#pragma unroll
+                for (int f = 0; f < PF; ++f)
+#pragma unroll
+                    for (int kh = 0; kh < 2; ++kh)
+                        af[(t + 1) & 1][f][kh] =
+                            *reinterpret_cast<const v4i *>(buf + frag_off[f] + tap_off + 32 * kh);
+            }
+            v4i wf[CT][2];
+#pragma unroll
+            for (int c = 0; c < CT; ++c) {
+                if (CONT == 4) {
+                    wf[c][0] = dsq_unpack16_c4((v2i){wreg[c][t][0], wreg[c][t][1]});
+                    wf[c][1] = dsq_unpack16_c4((v2i){wreg[c][t][CONT == 4 ? 2 : 0], wreg[c][t][CONT == 4 ? 3 : 1]});
+                } else {
+                    wf[c][0] = dsq_unpack2((uint32_t)wreg[c][t][0]);
+                    wf[c][1] = dsq_unpack2((uint32_t)wreg[c][t][1]);
+                }
+                if (HAS_NEXT) fetch_weight(c, t, next_cb);
+            }
+            // consecutive MFMAs go to different accumulators
+#pragma unroll
+            for (int kh = 0; kh < 2; ++kh)
+#pragma unroll
+                for (int c = 0; c < CT; ++c)
+#pragma unroll
+                    for (int f = 0; f < PF; ++f)
+                        acc[f][c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[c][kh], af[t & 1][f][kh], acc[f][c], 0, 0, 0);
+            // half way through the taps the next stage's patch has arrived:
+            // unpack it into the other buffer while the matrix cores are busy
+            if (HAS_NEXT && t == T / 2) store_patch(nextbuf);
+        }
+    };
+
+    DSQ_STAMP(1);
+    store_patch(lds);
+    {
+        int pp = UPP == 2 ? (tid >> 1) : tid;
+#pragma unroll
+        for (int k = 0; k < UPT; ++k) {
+            if (pp < pl.PR * pl.PC && (UPP == 1 || (tid & 1) == 0)) pix_lds[pp] = pix_val[k];
+            pp += 256 / UPP;
+        }
+        // Da*Dw[o] and Da*l_w[o] of this workgroup's channels, in binary64
+        const double da0 = (double)dsq_delta(a.l_a, a.u_a, (1 << a.bits) - 1);
+        if (tid < 2 * BC) pq_lds[tid] = da0 * (double)chan_const;
+    }
+    DSQ_STAMP(2);
+    __syncthreads();
+    DSQ_STAMP(3);
+
+    for (int cb = 0; cb < NCB - 1; ++cb) {
+        char *cur = lds + (cb & 1) * pl.buf_bytes;
+        char *nxt = lds + ((cb + 1) & 1) * pl.buf_bytes;
+        fetch_patch(cb + 1);
+        compute(std::true_type{}, cur, cb + 1, nxt);
+        DSQ_STAMP(4 + 2 * cb);
+        __syncthreads();
+        DSQ_STAMP(5 + 2 * cb);
+    }
+    compute(std::false_type{}, lds + ((NCB - 1) & 1) * pl.buf_bytes, 0, nullptr);
+    DSQ_STAMP(14);
+
+    // ---- epilogue (see conv_epilogue.h for the algebra) ------------------------
+    const int top = (1 << a.bits) - 1;
+    const float delta_a = dsq_delta(a.l_a, a.u_a, top);
+    // fast path: NHWC fp32 output only, l_a = 0, C_out a multiple of 4
+    const bool fast = !a.out_nchw && (a.C_out & 3) == 0 && a.l_a == 0.0f && a.acc == nullptr;
+
+    // per fragment: SA = code sums of the patch pixels under the taps (0 in the padding)
+    double dsa[PF];
+#pragma unroll
+    for (int f = 0; f < PF; ++f) {
+        int sa = 0;
+#pragma unroll
+        for (int t = 0; t < T; ++t) sa += pix_lds[frag_pp[f] + (t / R) * pl.PC + (t % R)];
+        dsa[f] = (double)sa;
+    }
+
+    // The results of a 32x32 tile sit in the lanes as [pixel = lane%32][4 groups
+    // of 4 channels].  They are staged through this wave's slice of the (now idle)
+    // patch buffers so that each store instruction writes the 32 consecutive
+    // channels (128 bytes) of 8 pixels instead of 16 bytes of 32 pixels.
+    constexpr int ROWB = 128 + 16;                // staged bytes per pixel (+16: bank spread)
+    constexpr int EPI_WAVE = 32 * ROWB + PF * 128;
+    __syncthreads();                              // every wave is done with the patch buffers
+    char *stage = lds + wave * EPI_WAVE;
+    int *m_stage = reinterpret_cast<int *>(stage + 32 * ROWB);
+
+    if (fast) {
+        if (h == 0) {
+#pragma unroll
+            for (int f = 0; f < PF; ++f) m_stage[f * 32 + col] = frag_m[f];
+        }
+#pragma unroll
+        for (int c = 0; c < CT; ++c) {
+            // Da*Dw and Da*l_w of this lane's channels of tile c: 4 groups of 4
+            double P[16], Q[16];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int ol = (wc * CT + c) * 32 + 8 * q + 4 * h;   // channel inside the workgroup
+#pragma unroll
+                for (int j = 0; j < 4; ++j) { P[4 * q + j] = pq_lds[ol + j]; Q[4 * q + j] = pq_lds[BC + ol + j]; }
+            }
+            const int o = (ct0 + c) * 32 + (lane & 7) * 4;   // channels this lane stores
+#pragma unroll
+            for (int f = 0; f < PF; ++f) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    double v[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        v[j] = __builtin_fma(P[4 * q + j], (double)acc[f][c][4 * q + j], Q[4 * q + j] * dsa[f]);
+                    *reinterpret_cast<float4 *>(stage + col * ROWB + (8 * q + 4 * h) * 4) =
+                        make_float4((float)v[0], (float)v[1], (float)v[2], (float)v[3]);
+                }
+                // (LDS operations of one wave execute in order: no barrier needed)
+                float4 rv[4];
+                int rm[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const int p = k * 8 + (lane >> 3);
+                    rv[k] = *reinterpret_cast<const float4 *>(stage + p * ROWB + (lane & 7) * 16);
+                    rm[k] = m_stage[f * 32 + p];
+                }
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    if (rm[k] >= 0 && o < a.C_out)
+                        *reinterpret_cast<float4 *>(a.out + (size_t)rm[k] * a.C_out + o) = rv[k];
+            }
+        }
+    } else {
+        // general path: l_a != 0 (terms that depend on which taps are inside the
+        // image), NCHW output, raw accumulators wanted, or C_out not a multiple of 4.
+        // (a private copy of the arguments, so that the kernel's own stay in
+        // scalar registers)
+        const DsqConvArgs a_copy = a;
+#pragma unroll
+        for (int f = 0; f < PF; ++f) {
+            const int m = frag_m[f];
+            if (m < 0) continue;
+#pragma unroll
+            for (int c = 0; c < CT; ++c)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int o0 = (ct0 + c) * 32 + 8 * q + 4 * h;
+                    if (o0 < a.C_out)
+                        store4_general(a_copy, m, o0,
+                                       (v4i){acc[f][c][4 * q], acc[f][c][4 * q + 1], acc[f][c][4 * q + 2], acc[f][c][4 * q + 3]},
+                                       delta_a);
+                }
+        }
+    }
+    DSQ_STAMP(15);
 }
 
 // ---- host side: tile planning and dispatch ---------------------------------
 
-struct TileCfg { int FRAGS, WP, WC, CT, UPT; };
-
-// Picks TR x TW (TR*TW <= BP) minimising padded work, then patch size.
-bool plan_patch(const DsqConvArgs &a, int BP, int UPT, int lds_limit, PatchPlan &best)
+// Picks the strip width TW minimising padded work, then patch size.
+int plan_lds_bytes(const PatchPlan &p, int BC)
 {
+    return p.aux_off + 2 * BC * 8 + p.PR * p.PC * 4;
+}
+
+bool plan_patch(const DsqConvArgs &a, int BP, int BC, int PF, int UPT, int lds_limit, PatchPlan &best)
+{
+    const int epi_bytes = 4 * (32 * (128 + 16) + PF * 128);   // epilogue staging of the four waves
     const int cont = dsq_container(a.bits);
     const int UPP = cont == 4 ? 2 : 1;
     const int NHo = a.N * a.Ho;
     const int Hp = a.H + 2 * a.pad;
     bool found = false;
     long long best_cost = 0;
-    for (int TW = 1; TW <= a.Wo && TW <= BP; ++TW) {
-        int TR = BP / TW;
-        if (TR > NHo) TR = NHo;
-        if (TR < 1) continue;
+    for (int TW = 1; TW <= a.Wo; ++TW) {
+        // widths that split the row evenly, the full row, or wide strips with a ragged last one
+        const int tiles_w = (a.Wo + TW - 1) / TW;
+        if (TW != a.Wo && a.Wo % TW != 0 && TW < 16) continue;
         PatchPlan p;
-        p.TR = TR; p.TW = TW; p.Hp = Hp;
-        p.tiles_w = (a.Wo + TW - 1) / TW;
-        p.row_tiles = (NHo + TR - 1) / TR;
+        p.TW = TW; p.BP = BP; p.Hp = Hp;
+        p.tiles_w = tiles_w;
+        const long long strip_pixels = (long long)NHo * TW;
+        if (strip_pixels + BP >= (1 << 22)) continue;          // fdiv operand range
+        p.row_tiles = (int)((strip_pixels + BP - 1) / BP);
         p.PC = (TW - 1) * a.stride + a.R;
         // patch rows: padded-row span of the tile's output rows, worst tile
         int PR = 0;
         for (int tr = 0; tr < p.row_tiles; ++tr) {
-            int g0 = tr * TR, g1 = g0 + TR - 1;
+            long long tA = (long long)tr * BP, tB = tA + BP - 1;
+            int g0 = (int)(tA / TW), g1 = (int)(tB / TW);
             if (g1 >= NHo) g1 = NHo - 1;
             int nA = g0 / a.Ho, nB = g1 / a.Ho;
             int vA = nA * Hp + (g0 - nA * a.Ho) * a.stride;
@@ -257,29 +468,34 @@ bool plan_patch(const DsqConvArgs &a, int BP, int UPT, int lds_limit, PatchPlan 
         }
         p.PR = PR;
         // row skew: consecutive tile pixels keep advancing by one pixel stride
-        // (mod 256 bytes) when a fragment wraps from one tile row to the next
+        // (mod 256 bytes) when a fragment wraps from one strip row to the next
         int skew = ((TW * a.stride - p.PC) * PIX_STRIDE) % 256;
         if (skew < 0) skew += 256;
-        // one output row down = `stride` patch rows down
-        // (for stride 2 the skew is split over the two rows; any remainder is harmless)
         p.RP = p.PC * PIX_STRIDE + (a.stride == 1 ? skew : 0);
-        p.buf_bytes = (p.PR * p.RP + 255) & ~255;
+        p.buf_bytes = (p.PR * p.RP + 64 + 255) & ~255;   // + dump slot for idle fetch units
         p.units = p.PR * p.PC * UPP;
-        if (2 * p.buf_bytes > lds_limit) continue;
+        p.inv_TW = 1.0f / (float)TW; p.inv_Hp = 1.0f / (float)Hp; p.inv_Ho = 1.0f / (float)a.Ho;
+        p.inv_PC = 1.0f / (float)p.PC; p.inv_tiles_w = 1.0f / (float)tiles_w;
+        p.step_q = (256 / UPP) / p.PC;
+        p.step_r = (256 / UPP) % p.PC;
+        p.aux_off = 2 * p.buf_bytes > epi_bytes ? 2 * p.buf_bytes : epi_bytes;
+        if (plan_lds_bytes(p, BC) > lds_limit) continue;
         if (p.units > 256 * UPT) continue;
         const long long tiles = (long long)p.tiles_w * p.row_tiles;
+        // index divisions in the kernel use float reciprocals: keep operands small
+        if (tiles >= (1 << 22) || (long long)a.N * Hp >= (1 << 22) || NHo >= (1 << 22)) continue;
         const long long cost = tiles * 100000 + (long long)p.PR * p.PC;
         if (!found || cost < best_cost) { best = p; best_cost = cost; found = true; }
     }
     return found;
 }
 
-template <int CONT, int R, int FRAGS, int WP, int WC, int CT, int UPT>
+template <int CONT, int R, int WP, int WC, int PF, int CT, int UPT>
 hipError_t launch_cfg(const DsqConvArgs &a, const PatchPlan &pl, hipStream_t stream)
 {
-    auto kern = conv_patch_kernel<CONT, R, FRAGS, WP, WC, CT, UPT>;
-    const int BC = 16 * CT * WC;
-    const size_t lds = 2 * (size_t)pl.buf_bytes;
+    auto kern = conv_patch_kernel<CONT, R, WP, WC, PF, CT, UPT>;
+    const int BC = 32 * CT * WC;
+    const size_t lds = (size_t)plan_lds_bytes(pl, BC);
     if (lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
@@ -289,38 +505,51 @@ hipError_t launch_cfg(const DsqConvArgs &a, const PatchPlan &pl, hipStream_t str
     return hipGetLastError();
 }
 
-// Tile shapes: small = 112 pixels x 64 channels, large = 224 x 128,
-// tall = 224 x 64 (for layers with few output channels).
-constexpr TileCfg kSmall = {7, 2, 2, 2, 4};
-constexpr TileCfg kLarge = {14, 2, 2, 4, 8};
-constexpr TileCfg kTall  = {14, 4, 1, 4, 8};
+// Tile shapes (pixels x channels per workgroup; per wave PF x CT MFMA tiles):
+//   small  128 x  64   waves 4x1, 1 x 2 tiles each  (few pixels: fill the chip)
+//   medium 128 x 128   waves 2x2, 2 x 2
+//   large  256 x 128   waves 2x2, 4 x 2
+struct TileCfg { int WP, WC, PF, CT, UPT; };
+constexpr TileCfg kSmall  = {4, 1, 1, 2, 4};
+constexpr TileCfg kMedium = {2, 2, 2, 2, 4};
+constexpr TileCfg kLarge  = {2, 2, 4, 2, 8};
 
-enum { TILE_SMALL = 0, TILE_LARGE = 1, TILE_TALL = 2 };
+enum { TILE_SMALL = 0, TILE_MEDIUM = 1, TILE_LARGE = 2 };
+
+const TileCfg &tile_cfg(int which)
+{
+    return which == TILE_LARGE ? kLarge : which == TILE_MEDIUM ? kMedium : kSmall;
+}
 
 int pick_tile(const DsqConvArgs &a)
 {
     const long long M = (long long)a.N * a.Ho * a.Wo;
-    const long long small_blocks = ((M + 111) / 112) * ((a.C_out + 63) / 64);
-    if (a.C_out <= 64) return small_blocks >= 2048 ? TILE_TALL : TILE_SMALL;
-    const long long large_blocks = ((M + 223) / 224) * ((a.C_out + 127) / 128);
-    return large_blocks >= 1024 ? TILE_LARGE : TILE_SMALL;
-}
-
-const TileCfg &tile_cfg(int which)
-{
-    return which == TILE_LARGE ? kLarge : which == TILE_TALL ? kTall : kSmall;
+    auto blocks = [&](const TileCfg &t) {
+        const long long bp = 32 * t.PF * t.WP, bc = 32 * t.CT * t.WC;
+        return ((M + bp - 1) / bp) * ((a.C_out + bc - 1) / bc);
+    };
+    if (a.C_out > 64 && blocks(kLarge) >= 512) return TILE_LARGE;
+    if (a.C_out > 64 && blocks(kMedium) >= 256) return TILE_MEDIUM;
+    return TILE_SMALL;
 }
 
 constexpr int kLdsLimit = 150 * 1024;
 
 }  // namespace
 
+#ifdef DSQ_TRACE
+extern "C" int dsq_trace_read(unsigned long long *host, size_t n)
+{
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(dsq_trace_buf), n * sizeof(unsigned long long));
+}
+#endif
+
 bool dsq_conv_patch_supported(const DsqConvArgs &a, int force_tile)
 {
     if ((long long)a.N * a.H * a.W * (a.Cp * dsq_container(a.bits) / 8) > 0x7FFFFFFFLL) return false;
     PatchPlan pl;
     const TileCfg &tc = tile_cfg(force_tile >= 0 ? force_tile : pick_tile(a));
-    return plan_patch(a, 16 * tc.FRAGS, tc.UPT, kLdsLimit, pl);
+    return plan_patch(a, 32 * tc.PF * tc.WP, 32 * tc.CT * tc.WC, tc.PF, tc.UPT, kLdsLimit, pl);
 }
 
 hipError_t dsq_launch_conv_patch(const DsqConvArgs &a, int force_tile, hipStream_t stream)
@@ -328,13 +557,13 @@ hipError_t dsq_launch_conv_patch(const DsqConvArgs &a, int force_tile, hipStream
     const int which = force_tile >= 0 ? force_tile : pick_tile(a);
     const TileCfg &tc = tile_cfg(which);
     PatchPlan pl;
-    if (!plan_patch(a, 16 * tc.FRAGS, tc.UPT, kLdsLimit, pl)) return hipErrorInvalidValue;
+    if (!plan_patch(a, 32 * tc.PF * tc.WP, 32 * tc.CT * tc.WC, tc.PF, tc.UPT, kLdsLimit, pl)) return hipErrorInvalidValue;
     const int cont = dsq_container(a.bits);
 #define DSQ_GO(CONT, RR)                                                                       \
     do {                                                                                       \
-        if (which == TILE_LARGE) return launch_cfg<CONT, RR, 14, 2, 2, 4, 8>(a, pl, stream);   \
-        if (which == TILE_TALL) return launch_cfg<CONT, RR, 14, 4, 1, 4, 8>(a, pl, stream);    \
-        return launch_cfg<CONT, RR, 7, 2, 2, 2, 4>(a, pl, stream);                             \
+        if (which == TILE_LARGE) return launch_cfg<CONT, RR, 2, 2, 4, 2, 8>(a, pl, stream);    \
+        if (which == TILE_MEDIUM) return launch_cfg<CONT, RR, 2, 2, 2, 2, 4>(a, pl, stream);   \
+        return launch_cfg<CONT, RR, 4, 1, 1, 2, 4>(a, pl, stream);                             \
     } while (0)
     if (cont == 4) { if (a.R == 3) DSQ_GO(4, 3); else DSQ_GO(4, 1); }
     else           { if (a.R == 3) DSQ_GO(2, 3); else DSQ_GO(2, 1); }

@@ -1,14 +1,15 @@
-// dsq_conv2d, simple kernel: one wavefront per 16-pixel x 16-channel output
+// dsq_conv2d, simple kernel: one wavefront per 32-pixel x 32-channel output
 // tile, operands fetched straight from global memory and unpacked in
 // registers.  It supports every geometry the library accepts and serves as the
 // fallback and as a cross-check for the tuned kernel.
 //
 // The GEMM view of Algorithm 1 step 5: rows = output channels, columns =
-// output pixels, K = taps x input channels.  v_mfma_i32_16x16x64_i8 takes, per
-// lane, 16 int8 of one row of the first operand (row = lane%16, K group =
-// lane/16) and 16 int8 of one column of the second (column = lane%16, same K
-// group), and leaves in lane L the int32 results of rows 4*(L/16)+0..3 of
-// column L%16 -- i.e. four consecutive output channels of one pixel.
+// output pixels, K = taps x input channels.  v_mfma_i32_32x32x32_i8 takes, per
+// lane, 16 int8 of one row of the first operand (row = lane%32, K group =
+// lane/32) and 16 int8 of one column of the second (column = lane%32, same K
+// group), and leaves in lane L, register r, the int32 result of row
+// 8*(r/4) + 4*(L/32) + r%4 of column L%32 -- i.e. four groups of four
+// consecutive output channels of one pixel.
 #include "conv_epilogue.h"
 
 namespace {
@@ -16,14 +17,15 @@ namespace {
 template <int CONT>
 __global__ __launch_bounds__(256) void conv_simple_kernel(DsqConvArgs a)
 {
-    constexpr int WPL = CONT == 4 ? 2 : 1;       // packed words per lane per K64 block
+    constexpr int WPL = CONT == 4 ? 2 : 1;       // packed words per lane per K half
     constexpr int KB_BYTES = 64 * CONT / 8;      // bytes of one pixel's 64-channel block
+    constexpr int KG_BYTES = 16 * CONT / 8;      // bytes of 16 channels
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int col = lane & 15, g = lane >> 4;
+    const int col = lane & 31, h = lane >> 5;
     const int M = a.N * a.Ho * a.Wo;
-    const int m = blockIdx.x * 16 + col;
+    const int m = blockIdx.x * 32 + col;
     const int ct = blockIdx.y * 4 + wave;
-    if (ct * 16 >= a.C_out) return;
+    if (ct * 32 >= a.C_out) return;
     const int T = a.R * a.R;
     const int NCB = a.Cp / 64;
     const int top = (1 << a.bits) - 1;
@@ -36,27 +38,37 @@ __global__ __launch_bounds__(256) void conv_simple_kernel(DsqConvArgs a)
     const char *act = (const char *)a.act;
     const uint32_t *wq = (const uint32_t *)a.wq;
 
-    v4i acc = {0, 0, 0, 0};
+    v16i acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0;
     for (int cb = 0; cb < NCB; ++cb) {
         for (int tap = 0; tap < T; ++tap) {
             const int r = tap / a.R, s = tap % a.R;
             const int iy = oy * a.stride - a.pad + r, ix = ox * a.stride - a.pad + s;
-            v4i af = {0, 0, 0, 0};
-            if (valid && iy >= 0 && iy < a.H && ix >= 0 && ix < a.W) {
-                const char *p = act + (((size_t)n * a.H + iy) * a.W + ix) * row_bytes +
-                                cb * KB_BYTES + g * (16 * CONT / 8);
-                if (CONT == 4) af = dsq_unpack16_c4(*reinterpret_cast<const v2i *>(p));
-                else af = dsq_unpack2(*reinterpret_cast<const uint32_t *>(p));
+            const bool inside = valid && iy >= 0 && iy < a.H && ix >= 0 && ix < a.W;
+            const char *p = act + (((size_t)n * a.H + iy) * a.W + ix) * row_bytes + cb * KB_BYTES;
+            const uint32_t *wp = wq + ((((size_t)ct * NCB + cb) * T + tap) * 64 + lane) * 2 * WPL;
+#pragma unroll
+            for (int kh = 0; kh < 2; ++kh) {
+                v4i af = {0, 0, 0, 0};
+                if (inside) {
+                    const char *pk = p + (2 * kh + h) * KG_BYTES;   // channels 32*kh + 16*h ..
+                    if (CONT == 4) af = dsq_unpack16_c4(*reinterpret_cast<const v2i *>(pk));
+                    else af = dsq_unpack2(*reinterpret_cast<const uint32_t *>(pk));
+                }
+                v4i wf;
+                if (CONT == 4) wf = dsq_unpack16_c4(*reinterpret_cast<const v2i *>(wp + kh * WPL));
+                else wf = dsq_unpack2(wp[kh * WPL]);
+                acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf, af, acc, 0, 0, 0);
             }
-            const uint32_t *wp = wq + ((((size_t)ct * NCB + cb) * T + tap) * 64 + lane) * WPL;
-            v4i wf;
-            if (CONT == 4) wf = dsq_unpack16_c4(*reinterpret_cast<const v2i *>(wp));
-            else wf = dsq_unpack2(*wp);
-            acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf, af, acc, 0, 0, 0);
         }
     }
     const DsqPixel px = dsq_pixel_info(a, m, M);
-    dsq_store4(a, px, m, ct * 16 + 4 * g, acc, delta_a);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const v4i part = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+        dsq_store4(a, px, m, ct * 32 + 8 * q + 4 * h, part, delta_a);
+    }
 }
 
 }  // namespace
@@ -64,7 +76,7 @@ __global__ __launch_bounds__(256) void conv_simple_kernel(DsqConvArgs a)
 hipError_t dsq_launch_conv_simple(const DsqConvArgs &a, hipStream_t stream)
 {
     const int M = a.N * a.Ho * a.Wo;
-    dim3 grid((M + 15) / 16, (a.C_out + 63) / 64);
+    dim3 grid((M + 31) / 32, (a.C_out + 127) / 128);
     if (dsq_container(a.bits) == 4) conv_simple_kernel<4><<<grid, 256, 0, stream>>>(a);
     else conv_simple_kernel<2><<<grid, 256, 0, stream>>>(a);
     return hipGetLastError();

@@ -5,6 +5,7 @@
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v2i __attribute__((ext_vector_type(2)));
+typedef int v16i __attribute__((ext_vector_type(16)));
 
 // Container width in bits for a given code width: 3-bit codes travel in
 // 4-bit containers.

@@ -8,8 +8,10 @@
 namespace {
 
 // One block per (padded) output channel o.  Output words of that channel:
-// (cb, tap, g, dd) -> 8 (4-bit) or 16 (2-bit) consecutive input channels
-// starting at 64*cb + 16*g + 8*dd.
+// (cb, tap, kh, h, dd) -> 8 (4-bit) or 16 (2-bit) consecutive input channels
+// starting at 64*cb + 32*kh + 16*h + 8*dd.  In memory the words of one
+// (32-channel tile, cb, tap) block are ordered [lane = 32*h + o%32][kh][dd], so
+// that a lane of the 32x32x32 MFMA finds its two K halves in 16 (8) adjacent bytes.
 template <int CONT>
 __global__ __launch_bounds__(256) void pack_weights_kernel(
     const float *__restrict__ w, const float *__restrict__ l_w, const float *__restrict__ u_w,
@@ -18,7 +20,7 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(
     int32_t *__restrict__ aux_total, int32_t *__restrict__ aux_tap)
 {
     constexpr int CPD = 32 / CONT;      // channels per word
-    constexpr int WPL = 16 / CPD;       // words per lane: 2 or 1
+    constexpr int WPL = 16 / CPD;       // words per lane per K half: 2 or 1
     __shared__ int stap[16];
     const int o = blockIdx.x;
     const int tid = threadIdx.x;
@@ -35,15 +37,16 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(
         const bool ok = (l < u) && (fabsf(l) <= 3.4028234e38f) && (fabsf(u) <= 3.4028234e38f);
         delta = ok ? dsq_delta(l, u, top) : __builtin_nanf("");
     }
-    const int ct = o >> 4, row = o & 15;
+    const int ct = o >> 5, row = o & 31;
     const int nwords = NCB * T * 4 * WPL;
     for (int i = tid; i < nwords; i += 256) {
         int dd = i % WPL;
         int rest = i / WPL;
-        int g = rest & 3; rest >>= 2;
+        int h = rest & 1; rest >>= 1;
+        int kh = rest & 1; rest >>= 1;
         int tap = rest % T;
         int cb = rest / T;
-        int c0 = 64 * cb + 16 * g + CPD * dd;
+        int c0 = 64 * cb + 32 * kh + 16 * h + CPD * dd;
         uint32_t word = 0;
         int s = 0;
         if (real) {
@@ -60,7 +63,7 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(
             }
             if (s) atomicAdd(&stap[tap], s);
         }
-        size_t dst = ((((size_t)ct * NCB + cb) * T + tap) * 64 + (16 * g + row)) * WPL + dd;
+        size_t dst = (((((size_t)ct * NCB + cb) * T + tap) * 64 + (32 * h + row)) * 2 + kh) * WPL + dd;
         wq[dst] = word;
     }
     __syncthreads();

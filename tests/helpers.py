@@ -42,11 +42,11 @@ def unpack_weights(packed_u8, C_out, C_in, R, bits):
     Cp, Cop = round_up(C_in, 64), round_up(C_out, 256)
     T = R * R
     wpl = 2 if container(bits) == 4 else 1
-    words = packed_u8.view(np.uint32).reshape(Cop // 16, Cp // 64, T, 64, wpl)
-    codes = unpack_words(words, bits)                 # [ct, cb, tap, lane, 16]
-    codes = codes.reshape(Cop // 16, Cp // 64, T, 4, 16, 16)   # lane = 16*g + row
-    # -> [ct, row, cb, g, k16, tap]
-    codes = codes.transpose(0, 4, 1, 3, 5, 2).reshape(Cop, Cp, R, R)
+    words = packed_u8.view(np.uint32).reshape(Cop // 32, Cp // 64, T, 64, 2, wpl)
+    codes = unpack_words(words, bits)                 # [ct, cb, tap, lane, kh, 16]
+    codes = codes.reshape(Cop // 32, Cp // 64, T, 2, 32, 2, 16)   # lane = 32*h + row
+    # axes: ct, cb, tap, h, row, kh, k16 -> channel = 64*cb + 32*kh + 16*h + k16
+    codes = codes.transpose(0, 4, 1, 5, 3, 6, 2).reshape(Cop, Cp, R, R)
     return codes
 
 

@@ -33,6 +33,10 @@ def _check_full(layer, inp, kernel, w_codes=None, **kw):
     da = oracle.delta(inp["l_a"], inp["u_a"], layer.bits)
     dw = [oracle.delta(float(a), float(b), layer.bits) for a, b in zip(inp["l_w"], inp["u_w"])]
     assert_out_close(got["out"], ref, da, dw)
+    # without the raw-accumulator output the kernels may take a different
+    # (faster) store path: check that one too
+    got2 = _run(layer, inp, kernel, w_codes=w_codes, with_acc=False, **kw)
+    assert_out_close(got2["out"], ref, da, dw)
     return got, ref
 
 
@@ -96,6 +100,7 @@ def test_config_1_and_2_full_tensors(cfg, kernel):
 
 def _check_sampled(layer, inp, kernel, nsamples=4000):
     got = _run(layer, inp, kernel)
+    fast = _run(layer, inp, kernel, with_acc=False)["out"]     # the store path bench.py times
     a_code, w_code = oracle_layer(layer, inp)
     total = got["out"].size
     rng = np.random.default_rng(layer.C_in + layer.H + layer.bits)
@@ -112,9 +117,12 @@ def _check_sampled(layer, inp, kernel, nsamples=4000):
     o_of = (idx // (Ho * Wo)) % Co
     da = oracle.delta(inp["l_a"], inp["u_a"], layer.bits)
     dw = np.array([oracle.delta(float(inp["l_w"][o]), float(inp["u_w"][o]), layer.bits) for o in o_of])
-    g = got["out"].reshape(-1)[idx].astype(np.float64)
     r = vals.astype(np.float64)
-    assert np.all(np.abs(g - r) <= 1e-5 * np.abs(r) + 1e-5 * da * dw)
+    for out in (got["out"], fast):
+        g = out.reshape(-1)[idx].astype(np.float64)
+        assert np.all(np.abs(g - r) <= 1e-5 * np.abs(r) + 1e-5 * da * dw)
+    # both store paths evaluate the same expression: identical everywhere
+    assert np.array_equal(got["out"], fast)
     # properties that hold at any size: finite everywhere, accumulators within
     # the closed-form bound (2^b-1)^2 * K
     assert np.isfinite(got["out"]).all()
