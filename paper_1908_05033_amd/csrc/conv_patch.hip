@@ -33,6 +33,14 @@
 
 namespace {
 
+#ifndef DSQ_MED_WD
+#define DSQ_MED_WD 3
+#define DSQ_MED_OCC 3
+#endif
+#ifndef DSQ_STORE_TAP
+#define DSQ_STORE_TAP (T / 2)
+#endif
+
 constexpr int PIX_STRIDE = 80;   // LDS bytes per patch pixel (64 used)
 
 #ifdef DSQ_TRACE
@@ -81,8 +89,8 @@ __device__ __noinline__ void store4_general(const DsqConvArgs &a, int m, int o0,
     dsq_store4(a, px, m, o0, acc, delta_a);
 }
 
-template <int CONT, int R, int WP, int WC, int PF, int CT, int UPT>
-__global__ __launch_bounds__(256) void conv_patch_kernel(DsqConvArgs a, PatchPlan pl)
+template <int CONT, int R, int WP, int WC, int PF, int CT, int UPT, int WD, int OCC>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OCC, OCC))) void conv_patch_kernel(DsqConvArgs a, PatchPlan pl)
 {
     constexpr int T = R * R;
     constexpr int UPP = CONT == 4 ? 2 : 1;        // 16-byte fetch units per patch pixel
@@ -130,25 +138,22 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(DsqConvArgs a, PatchPla
     // lane-ordered fragments, [ct][cb][tap][lane][both K halves]
     const int ct0 = (blockIdx.y * WC + wc) * CT;
     const uint32_t lane_woff = (uint32_t)lane * WLANE;
-    wpack_t wreg[CT][T];     // packed weight fragments of the current stage; each is
-                             // refilled for the next stage as soon as it has been used
+    // Packed weight fragments travel WD taps ahead of their use in a ring of
+    // registers (slot = tap % WD; WD divides the tap count); a slot is refilled as
+    // soon as it has been unpacked.
+    static_assert(T % WD == 0, "ring period must divide the taps of a stage");
+    wpack_t wreg[CT][WD];
     auto fetch_weight = [&](int c, int t, int cb) {
         const char *p = (const char *)a.wq +
                         ((((size_t)(ct0 + c) * NCB + cb) * T + t) * 64) * WLANE + lane_woff;
-        wreg[c][t] = *reinterpret_cast<const wpack_t *>(p);
+        wreg[c][t % WD] = *reinterpret_cast<const wpack_t *>(p);
     };
 #pragma unroll
     for (int c = 0; c < CT; ++c)
 #pragma unroll
-        for (int t = 0; t < T; ++t) fetch_weight(c, t, 0);
+        for (int t = 0; t < WD; ++t) fetch_weight(c, t, 0);
 
     DSQ_STAMP(10);
-    // per-channel dequantization constants of this workgroup's channels -> LDS
-    float chan_const = 0.f;
-    if (tid < 2 * BC) {
-        const int o = blockIdx.y * BC + (tid < BC ? tid : tid - BC);      // < Cop by construction
-        chan_const = tid < BC ? a.delta_w[o] : a.l_w[o];
-    }
 
     // ---- tile position -------------------------------------------------------
     int tile_w;
@@ -164,37 +169,34 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(DsqConvArgs a, PatchPla
     const uint32_t row_bytes = (uint32_t)a.Cp * CONT / 8;
 
     // ---- per-thread fetch units of the patch ---------------------------------
-    // unit u = tid + 256*k covers half `u % UPP` of patch pixel u / UPP
+    // unit u = tid + 256*k covers half `u % UPP` of patch pixel u / UPP; (prow, pcol)
+    // and the image row behind prow advance by fixed steps from unit to unit
     uint32_t src_off[UPT];   // byte offset into act of the unit at channel block 0
+    uint32_t src_pix[UPT];   // index of the unit's input pixel (0 if none)
     int dst_off[UPT];        // LDS byte offset inside a patch buffer (dump slot if no such unit)
-    int pix_val[UPT];        // code sum of the unit's pixel (first half-unit only)
     uint32_t src_valid = 0;  // bit k: unit k reads real data (else: zero padding)
     const int dump_off = pl.buf_bytes - 64;
+    const int half = UPP == 2 ? (tid & 1) : 0;
     {
-        const int half = UPP == 2 ? (tid & 1) : 0;
-        int pcol;
+        int pcol, ihp;
         int prow = fdiv(UPP == 2 ? (tid >> 1) : tid, pl.PC, pl.inv_PC, pcol);
+        int n = fdiv(v0 + prow, pl.Hp, pl.inv_Hp, ihp);
 #pragma unroll
         for (int k = 0; k < UPT; ++k) {
-            src_off[k] = 0;
-            dst_off[k] = dump_off;
-            pix_val[k] = 0;
-            if (prow < pl.PR) {
-                dst_off[k] = prow * pl.RP + pcol * PIX_STRIDE + half * 32;
-                int ihp;
-                const int n = fdiv(v0 + prow, pl.Hp, pl.inv_Hp, ihp);
-                const int ih = ihp - a.pad;
-                const int iw = vc0 + pcol - a.pad;
-                if (n < a.N && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W) {
-                    const uint32_t pix = (uint32_t)((n * a.H + ih) * a.W + iw);
-                    src_off[k] = pix * row_bytes + half * 16;
-                    src_valid |= 1u << k;
-                    if (half == 0) pix_val[k] = a.pix_sum[pix];
-                }
-            }
-            prow += pl.step_q;
+            const int ih = ihp - a.pad, iw = vc0 + pcol - a.pad;
+            const bool inpatch = prow < pl.PR;
+            const bool valid = inpatch && n < a.N && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
+            const uint32_t pix = valid ? (uint32_t)((n * a.H + ih) * a.W + iw) : 0u;
+            src_pix[k] = pix;
+            src_off[k] = pix * row_bytes + half * 16;
+            dst_off[k] = inpatch ? prow * pl.RP + pcol * PIX_STRIDE + half * 32 : dump_off;
+            src_valid |= (valid ? 1u : 0u) << k;
+            int dp = pl.step_q;
             pcol += pl.step_r;
-            if (pcol >= pl.PC) { pcol -= pl.PC; ++prow; }
+            if (pcol >= pl.PC) { pcol -= pl.PC; ++dp; }
+            prow += dp;
+            ihp += dp;
+            while (ihp >= pl.Hp) { ihp -= pl.Hp; ++n; }  // seldom more than once
         }
     }
 
@@ -224,6 +226,16 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(DsqConvArgs a, PatchPla
     };
     fetch_patch(0);
     DSQ_STAMP(13);
+    // side tables, needed only after the main loop: the pixels' code sums and the
+    // per-channel dequantization constants of this workgroup's channels
+    int pix_val[UPT];
+#pragma unroll
+    for (int k = 0; k < UPT; ++k) pix_val[k] = a.pix_sum[src_pix[k]];
+    float chan_const = 0.f;
+    if (tid < 2 * BC) {
+        const int o = blockIdx.y * BC + (tid < BC ? tid : tid - BC);      // < Cop by construction
+        chan_const = tid < BC ? a.delta_w[o] : a.l_w[o];
+    }
 
     // ---- per-lane LDS offsets of the fragments' pixels -----------------------
     // Tile pixels past the end of the strip multiply patch pixel 0 and are
@@ -259,7 +271,7 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(DsqConvArgs a, PatchPla
 
     // One stage: all taps of 64 input channels.  HAS_NEXT: the weights and the
     // patch of stage next_cb are fetched / stored on the way.
-    auto compute = [&](auto has_next, const char *buf, int next_cb, char *nextbuf) {
+    auto compute = [&](auto has_next, const char *buf, int cur_cb, int next_cb, char *nextbuf) {
         constexpr bool HAS_NEXT = decltype(has_next)::value;
         v4i af[2][PF][2];
 #pragma unroll
@@ -281,14 +293,18 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(DsqConvArgs a, PatchPla
             v4i wf[CT][2];
 #pragma unroll
             for (int c = 0; c < CT; ++c) {
+                const wpack_t wr = wreg[c][t % WD];
                 if (CONT == 4) {
-                    wf[c][0] = dsq_unpack16_c4((v2i){wreg[c][t][0], wreg[c][t][1]});
-                    wf[c][1] = dsq_unpack16_c4((v2i){wreg[c][t][CONT == 4 ? 2 : 0], wreg[c][t][CONT == 4 ? 3 : 1]});
+                    wf[c][0] = dsq_unpack16_c4((v2i){wr[0], wr[1]});
+                    wf[c][1] = dsq_unpack16_c4((v2i){wr[CONT == 4 ? 2 : 0], wr[CONT == 4 ? 3 : 1]});
                 } else {
-                    wf[c][0] = dsq_unpack2((uint32_t)wreg[c][t][0]);
-                    wf[c][1] = dsq_unpack2((uint32_t)wreg[c][t][1]);
+                    wf[c][0] = dsq_unpack2((uint32_t)wr[0]);
+                    wf[c][1] = dsq_unpack2((uint32_t)wr[1]);
                 }
-                if (HAS_NEXT) fetch_weight(c, t, next_cb);
+#ifndef DSQ_DBG_NO_WEIGHT_REFILL
+                if (t + WD < T) fetch_weight(c, t + WD, cur_cb);
+                else if (HAS_NEXT) fetch_weight(c, t + WD - T, next_cb);
+#endif
             }
             // consecutive MFMAs go to different accumulators
 #pragma unroll
@@ -296,11 +312,18 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(DsqConvArgs a, PatchPla
 #pragma unroll
                 for (int c = 0; c < CT; ++c)
 #pragma unroll
-                    for (int f = 0; f < PF; ++f)
+                    for (int f = 0; f < PF; ++f) {
+#ifndef DSQ_DBG_NO_MFMA
                         acc[f][c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[c][kh], af[t & 1][f][kh], acc[f][c], 0, 0, 0);
+#else
+                        acc[f][c][0] += wf[c][kh][0] + af[t & 1][f][kh][0];
+#endif
+                    }
             // half way through the taps the next stage's patch has arrived:
             // unpack it into the other buffer while the matrix cores are busy
-            if (HAS_NEXT && t == T / 2) store_patch(nextbuf);
+#ifndef DSQ_DBG_NO_PATCH_REFILL
+            if (HAS_NEXT && t == DSQ_STORE_TAP) store_patch(nextbuf);
+#endif
         }
     };
 
@@ -310,7 +333,7 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(DsqConvArgs a, PatchPla
         int pp = UPP == 2 ? (tid >> 1) : tid;
 #pragma unroll
         for (int k = 0; k < UPT; ++k) {
-            if (pp < pl.PR * pl.PC && (UPP == 1 || (tid & 1) == 0)) pix_lds[pp] = pix_val[k];
+            if (pp < pl.PR * pl.PC && half == 0) pix_lds[pp] = (src_valid >> k & 1) ? pix_val[k] : 0;
             pp += 256 / UPP;
         }
         // Da*Dw[o] and Da*l_w[o] of this workgroup's channels, in binary64
@@ -324,13 +347,15 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(DsqConvArgs a, PatchPla
     for (int cb = 0; cb < NCB - 1; ++cb) {
         char *cur = lds + (cb & 1) * pl.buf_bytes;
         char *nxt = lds + ((cb + 1) & 1) * pl.buf_bytes;
+#ifndef DSQ_DBG_NO_PATCH_REFILL
         fetch_patch(cb + 1);
-        compute(std::true_type{}, cur, cb + 1, nxt);
+#endif
+        compute(std::true_type{}, cur, cb, cb + 1, nxt);
         DSQ_STAMP(4 + 2 * cb);
         __syncthreads();
         DSQ_STAMP(5 + 2 * cb);
     }
-    compute(std::false_type{}, lds + ((NCB - 1) & 1) * pl.buf_bytes, 0, nullptr);
+    compute(std::false_type{}, lds + ((NCB - 1) & 1) * pl.buf_bytes, NCB - 1, 0, nullptr);
     DSQ_STAMP(14);
 
     // ---- epilogue (see conv_epilogue.h for the algebra) ------------------------
@@ -484,16 +509,20 @@ bool plan_patch(const DsqConvArgs &a, int BP, int BC, int PF, int UPT, int lds_l
         const long long tiles = (long long)p.tiles_w * p.row_tiles;
         // index divisions in the kernel use float reciprocals: keep operands small
         if (tiles >= (1 << 22) || (long long)a.N * Hp >= (1 << 22) || NHo >= (1 << 22)) continue;
-        const long long cost = tiles * 100000 + (long long)p.PR * p.PC;
+        // equal work: prefer a footprint that lets three (else two) workgroups share a CU,
+        // then the smaller patch
+        const int lds_bytes = plan_lds_bytes(p, BC);
+        const long long cost = tiles * 100000 + (lds_bytes <= 52 * 1024 ? 0 : lds_bytes <= 78 * 1024 ? 20000 : 40000) +
+                               (long long)p.PR * p.PC;
         if (!found || cost < best_cost) { best = p; best_cost = cost; found = true; }
     }
     return found;
 }
 
-template <int CONT, int R, int WP, int WC, int PF, int CT, int UPT>
+template <int CONT, int R, int WP, int WC, int PF, int CT, int UPT, int WD, int OCC>
 hipError_t launch_cfg(const DsqConvArgs &a, const PatchPlan &pl, hipStream_t stream)
 {
-    auto kern = conv_patch_kernel<CONT, R, WP, WC, PF, CT, UPT>;
+    auto kern = conv_patch_kernel<CONT, R, WP, WC, PF, CT, UPT, WD, OCC>;
     const int BC = 32 * CT * WC;
     const size_t lds = (size_t)plan_lds_bytes(pl, BC);
     if (lds > 64 * 1024) {
@@ -561,9 +590,10 @@ hipError_t dsq_launch_conv_patch(const DsqConvArgs &a, int force_tile, hipStream
     const int cont = dsq_container(a.bits);
 #define DSQ_GO(CONT, RR)                                                                       \
     do {                                                                                       \
-        if (which == TILE_LARGE) return launch_cfg<CONT, RR, 2, 2, 4, 2, 8>(a, pl, stream);    \
-        if (which == TILE_MEDIUM) return launch_cfg<CONT, RR, 2, 2, 2, 2, 4>(a, pl, stream);   \
-        return launch_cfg<CONT, RR, 4, 1, 1, 2, 4>(a, pl, stream);                             \
+        constexpr int WD = RR == 3 ? 3 : 1;                                                    \
+        if (which == TILE_LARGE) return launch_cfg<CONT, RR, 2, 2, 4, 2, 8, WD, 2>(a, pl, stream);  \
+        if (which == TILE_MEDIUM) return launch_cfg<CONT, RR, 2, 2, 2, 2, 4, (RR == 3 ? DSQ_MED_WD : 1), DSQ_MED_OCC>(a, pl, stream); \
+        return launch_cfg<CONT, RR, 4, 1, 1, 2, 4, WD, 3>(a, pl, stream);                           \
     } while (0)
     if (cont == 4) { if (a.R == 3) DSQ_GO(4, 3); else DSQ_GO(4, 1); }
     else           { if (a.R == 3) DSQ_GO(2, 3); else DSQ_GO(2, 1); }
