@@ -37,8 +37,12 @@ namespace {
 #define DSQ_MED_WD 3
 #define DSQ_MED_OCC 3
 #endif
+#ifndef DSQ_SMALL_WD
+#define DSQ_SMALL_WD 3
+#define DSQ_SMALL_OCC 3
+#endif
 #ifndef DSQ_STORE_TAP
-#define DSQ_STORE_TAP (T / 2)
+#define DSQ_STORE_TAP (WD == T ? T - 1 : T / 2)
 #endif
 
 constexpr int PIX_STRIDE = 80;   // LDS bytes per patch pixel (64 used)
@@ -48,8 +52,8 @@ constexpr int PIX_STRIDE = 80;   // LDS bytes per patch pixel (64 used)
 __device__ unsigned long long dsq_trace_buf[4096 * 16];
 #define DSQ_STAMP(slot)                                                              \
     do {                                                                             \
-        if (lane == 0 && blockIdx.y == 0 && blockIdx.x < 1024 && (slot) < 16)        \
-            dsq_trace_buf[(blockIdx.x * 4 + wave) * 16 + (slot)] = __builtin_amdgcn_s_memtime(); \
+        if (lane == 0 && blk_y == 0 && blk_x < 1024 && (slot) < 16)                  \
+            dsq_trace_buf[(blk_x * 4 + wave) * 16 + (slot)] = __builtin_amdgcn_s_memtime(); \
     } while (0)
 #else
 #define DSQ_STAMP(slot) do { } while (0)
@@ -66,6 +70,10 @@ struct PatchPlan {
     int Hp;            // H + 2*pad: rows of one image in the padded row space
     int units;         // 16-byte fetch units per stage
     int aux_off;       // LDS offset of the small tables that follow the patch / staging area
+    int tiles_c;       // channel tiles (workgroups per pixel tile)
+    int total_blocks;  // pixel tiles * channel tiles
+    int xcd_chunk;     // ceil(total_blocks / 8)
+    float inv_tiles_c;
     int step_q, step_r;   // (256 / units-per-pixel) divided by PC: quotient and remainder
     float inv_PC, inv_TW, inv_Hp, inv_Ho, inv_tiles_w;   // reciprocals for the index divisions
 };
@@ -113,6 +121,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OCC, OCC)))
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 31, h = lane >> 5;
     const int wp = wave % WP, wc = wave / WP;
+
+    // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Give
+    // every XCD a contiguous range of tiles, channel tiles of one pixel tile
+    // first, so that the tiles that share activations (same pixels, halo rows of
+    // neighbours) meet in one L2.
+    const int logical = ((int)blockIdx.x & 7) * pl.xcd_chunk + ((int)blockIdx.x >> 3);
+    if (logical >= pl.total_blocks) return;
+    int blk_y;
+    const int blk_x = fdiv(logical, pl.tiles_c, pl.inv_tiles_c, blk_y);
     DSQ_STAMP(0);
 
     // The kernel arguments live in memory that is slow to reach; touching all of
@@ -125,7 +142,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OCC, OCC)))
             (long long)(intptr_t)a.wq + (long long)(intptr_t)a.delta_w + (long long)(intptr_t)a.l_w +
             (long long)(intptr_t)a.out + (long long)(intptr_t)a.acc + (long long)(intptr_t)a.sw_total +
             (long long)(intptr_t)a.sw_tap + a.R + a.Cop + pl.TW + pl.BP + pl.tiles_w + pl.PR + pl.PC +
-            pl.RP + pl.buf_bytes + pl.Hp + pl.units + pl.aux_off + pl.step_q + pl.step_r +
+            pl.RP + pl.buf_bytes + pl.Hp + pl.units + pl.aux_off + pl.step_q + pl.step_r + pl.tiles_c +
+            pl.total_blocks + pl.xcd_chunk + __float_as_int(pl.inv_tiles_c) +
             (long long)__float_as_int(pl.inv_PC) + __float_as_int(pl.inv_TW) + __float_as_int(pl.inv_Hp) +
             __float_as_int(pl.inv_Ho) + __float_as_int(pl.inv_tiles_w) + __float_as_int(a.l_a) + __float_as_int(a.u_a);
         if (a.N == 0 && touch == 0x7FFFFFFFFFFFFFFFLL) return;
@@ -136,7 +154,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OCC, OCC)))
 
     // ---- weights first: their addresses need only the lane and block ids ----
     // lane-ordered fragments, [ct][cb][tap][lane][both K halves]
-    const int ct0 = (blockIdx.y * WC + wc) * CT;
+    const int ct0 = (blk_y * WC + wc) * CT;
     const uint32_t lane_woff = (uint32_t)lane * WLANE;
     // Packed weight fragments travel WD taps ahead of their use in a ring of
     // registers (slot = tap % WD; WD divides the tap count); a slot is refilled as
@@ -157,7 +175,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OCC, OCC)))
 
     // ---- tile position -------------------------------------------------------
     int tile_w;
-    const int tile_r = fdiv((int)blockIdx.x, pl.tiles_w, pl.inv_tiles_w, tile_w);
+    const int tile_r = fdiv(blk_x, pl.tiles_w, pl.inv_tiles_w, tile_w);
     const int t0 = tile_r * pl.BP;              // first pixel of the tile, numbered inside the strip
     const int ow0 = tile_w * pl.TW;
     int tc0;
@@ -233,7 +251,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OCC, OCC)))
     for (int k = 0; k < UPT; ++k) pix_val[k] = a.pix_sum[src_pix[k]];
     float chan_const = 0.f;
     if (tid < 2 * BC) {
-        const int o = blockIdx.y * BC + (tid < BC ? tid : tid - BC);      // < Cop by construction
+        const int o = blk_y * BC + (tid < BC ? tid : tid - BC);      // < Cop by construction
         chan_const = tid < BC ? a.delta_w[o] : a.l_w[o];
     }
 
@@ -508,7 +526,7 @@ bool plan_patch(const DsqConvArgs &a, int BP, int BC, int PF, int UPT, int lds_l
         if (p.units > 256 * UPT) continue;
         const long long tiles = (long long)p.tiles_w * p.row_tiles;
         // index divisions in the kernel use float reciprocals: keep operands small
-        if (tiles >= (1 << 22) || (long long)a.N * Hp >= (1 << 22) || NHo >= (1 << 22)) continue;
+        if (tiles * ((a.C_out + BC - 1) / BC) >= (1 << 22) || (long long)a.N * Hp >= (1 << 22) || NHo >= (1 << 22)) continue;
         // equal work: prefer a footprint that lets three (else two) workgroups share a CU,
         // then the smaller patch
         const int lds_bytes = plan_lds_bytes(p, BC);
@@ -529,8 +547,12 @@ hipError_t launch_cfg(const DsqConvArgs &a, const PatchPlan &pl, hipStream_t str
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    dim3 grid(pl.tiles_w * pl.row_tiles, (a.C_out + BC - 1) / BC);
-    kern<<<grid, 256, lds, stream>>>(a, pl);
+    PatchPlan p2 = pl;
+    p2.tiles_c = (a.C_out + BC - 1) / BC;
+    p2.inv_tiles_c = 1.0f / (float)p2.tiles_c;
+    p2.total_blocks = pl.tiles_w * pl.row_tiles * p2.tiles_c;
+    p2.xcd_chunk = (p2.total_blocks + 7) / 8;
+    kern<<<dim3(8 * p2.xcd_chunk), 256, lds, stream>>>(a, p2);
     return hipGetLastError();
 }
 
@@ -593,7 +615,7 @@ hipError_t dsq_launch_conv_patch(const DsqConvArgs &a, int force_tile, hipStream
         constexpr int WD = RR == 3 ? 3 : 1;                                                    \
         if (which == TILE_LARGE) return launch_cfg<CONT, RR, 2, 2, 4, 2, 8, WD, 2>(a, pl, stream);  \
         if (which == TILE_MEDIUM) return launch_cfg<CONT, RR, 2, 2, 2, 2, 4, (RR == 3 ? DSQ_MED_WD : 1), DSQ_MED_OCC>(a, pl, stream); \
-        return launch_cfg<CONT, RR, 4, 1, 1, 2, 4, WD, 3>(a, pl, stream);                           \
+        return launch_cfg<CONT, RR, 4, 1, 1, 2, 4, (RR == 3 ? DSQ_SMALL_WD : 1), DSQ_SMALL_OCC>(a, pl, stream); \
     } while (0)
     if (cont == 4) { if (a.R == 3) DSQ_GO(4, 3); else DSQ_GO(4, 1); }
     else           { if (a.R == 3) DSQ_GO(2, 3); else DSQ_GO(2, 1); }

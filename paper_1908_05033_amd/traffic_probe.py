@@ -1,0 +1,60 @@
+"""Workload for HBM-traffic counters (run under ``rocprofv3 --pmc FETCH_SIZE``
+or ``--pmc WRITE_SIZE``):
+
+    rocprofv3 --pmc FETCH_SIZE --output-format csv -d out -- \\
+        python3 -m paper_1908_05033_amd.traffic_probe --cfg 2
+
+It launches (1) a plain device-to-device copy of a known size, which calibrates
+the counter (bytes the counter reports per byte really moved), and (2) the
+quantize and convolution kernels of the first layer of a config, each over
+several distinct buffer sets so that the last-level cache cannot serve them.
+"""
+import argparse
+
+import torch
+
+from . import binding as B
+from . import inputs
+
+COPY_BYTES = 256 * 1024 * 1024
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--cfg", type=int, default=2)
+    ap.add_argument("--layer", type=int, default=0)
+    ap.add_argument("--sets", type=int, default=48)
+    a = ap.parse_args()
+    L = inputs.config_layers(a.cfg)[a.layer]
+    dev = "cuda"
+    gen = torch.Generator(device=dev).manual_seed(inputs.BASE_SEED)
+
+    src = torch.empty(COPY_BYTES // 4, dtype=torch.float32, device=dev).normal_(generator=gen)
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)            # calibration: reads and writes COPY_BYTES
+    torch.cuda.synchronize()
+
+    w = torch.randn((L.C_out, L.C_in, L.R, L.S), device=dev, generator=gen) * 0.05
+    uw = w.reshape(L.C_out, -1).abs().amax(dim=1).contiguous()
+    lw = (-uw).contiguous()
+    bufs = []
+    for _ in range(a.sets):
+        b = B.alloc_layer(L.N, L.C_in, L.H, L.W, L.C_out, L.R, L.S, L.stride, L.pad, L.bits)
+        b.x = torch.randn((L.N, L.H, L.W, L.C_in), device=dev, generator=gen).abs_()
+        bufs.append(b)
+    wp, aux = bufs[0].w_packed, bufs[0].w_aux
+    B.dsq_pack_weights(w, lw, uw, None, L.C_out, L.C_in, L.R, L.S, L.bits, wp, aux)
+    torch.cuda.synchronize()
+    for b in bufs:
+        B.dsq_quantize_act(b.x, B.DSQ_NHWC, L.N, L.C_in, L.H, L.W, 0.0, 2.5, L.bits,
+                           b.act_packed, b.pix_code_sum)
+    torch.cuda.synchronize()
+    for b in bufs:
+        B.dsq_conv2d(b.desc, b.act_packed, b.pix_code_sum, 0.0, 2.5, wp, aux, b.out, B.DSQ_NHWC, None)
+    torch.cuda.synchronize()
+    print("copy_bytes", COPY_BYTES, "layer", L.name, "sets", a.sets)
+
+
+if __name__ == "__main__":
+    main()
