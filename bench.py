@@ -37,6 +37,7 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--config", type=int, default=2, help="BASELINE config (1 or 2)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--serial", action="store_true", help="no overlap between steps of different batches")
     ap.add_argument("--sets", type=int, default=0, help="buffer sets to rotate over (0 = auto)")
     return ap.parse_args()
 
@@ -102,6 +103,35 @@ def main():
                 fn(b)
         return g
 
+    side = torch.cuda.Stream()
+
+    def capture_pipelined():
+        """All steps of one pass over the buffer sets, software-pipelined over two
+        streams the way a serving loop double-buffers batches: the activations of
+        batch i+1 are quantized (side stream) while batch i is convolved (launch
+        stream).  Every step still runs quantize then conv on its own batch; only
+        steps of different batches overlap."""
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=stream):
+            ready = []
+            side.wait_stream(stream)
+            with torch.cuda.stream(side):
+                quant(bufs[0])
+                e = torch.cuda.Event()
+                e.record(side)
+                ready.append(e)
+            for i, b in enumerate(bufs):
+                if i + 1 < len(bufs):
+                    with torch.cuda.stream(side):
+                        quant(bufs[i + 1])
+                        e = torch.cuda.Event()
+                        e.record(side)
+                        ready.append(e)
+                stream.wait_event(ready[i])
+                conv(b)
+            stream.wait_stream(side)
+        return g
+
     def timed_replays(g, n):
         """n replays of a graph between two events on the launch stream."""
         with torch.cuda.stream(stream):
@@ -132,19 +162,23 @@ def main():
         conv(b)
 
     g_step, g_quant, g_conv = capture(step), capture(quant), capture(conv)
+    g_pipe = capture_pipelined() if not args.serial else g_step
 
     # ---- the timed region: exactly `steps` steps ---------------------------
     n_warm = max(1, -(-args.warmup // sets))
     n_rep = max(1, -(-args.steps // sets))
     steps = n_rep * sets
     warmup = n_warm * sets
-    timed_replays(g_step, n_warm)
+    timed_replays(g_pipe, n_warm)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    gpu_s = timed_replays(g_step, n_rep)
+    gpu_s = timed_replays(g_pipe, n_rep)
     wall_s = time.perf_counter() - t0
     step_s = max(gpu_s, 0.0) / steps
     value = 2.0 * macs / step_s / 1e12
+    # the same steps strictly one after the other on one stream
+    timed_replays(g_step, n_warm)
+    serial_step_s = timed_replays(g_step, n_rep) / steps
 
     # ---- per-kernel average launch durations, same stream, HIP events ------
     timed_replays(g_conv, n_warm)
@@ -175,9 +209,12 @@ def main():
             "gemm_MxNxK": [L.N * L.Ho * L.Wo, L.C_out, L.C_in * L.R * L.S],
             "macs_per_step": macs,
             "buffer_sets": sets,
-            "launch": "hipGraph of %d steps replayed %d times" % (sets, n_rep),
+            "launch": ("hipGraph of %d steps replayed %d times; " % (sets, n_rep)) +
+                      ("steps strictly serial on one stream" if args.serial else
+                       "quantize of batch i+1 overlaps conv of batch i (two streams)"),
         },
         "kernels": {
+            "serial_step_us": round(serial_step_s * 1e6, 3),
             "dsq_conv2d_us": round(conv_s * 1e6, 3),
             "dsq_conv2d_TOPS": round(conv_tops, 2),
             "dsq_quantize_act_us": round(quant_s * 1e6, 3),

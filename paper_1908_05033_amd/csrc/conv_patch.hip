@@ -37,6 +37,12 @@ namespace {
 #define DSQ_MED_WD 3
 #define DSQ_MED_OCC 3
 #endif
+#ifndef DSQ_S_WP
+#define DSQ_S_WP 4
+#define DSQ_S_WC 1
+#define DSQ_S_PF 1
+#define DSQ_S_CT 2
+#endif
 #ifndef DSQ_SMALL_WD
 #define DSQ_SMALL_WD 3
 #define DSQ_SMALL_OCC 3
@@ -77,6 +83,14 @@ struct PatchPlan {
     int step_q, step_r;   // (256 / units-per-pixel) divided by PC: quotient and remainder
     float inv_PC, inv_TW, inv_Hp, inv_Ho, inv_tiles_w;   // reciprocals for the index divisions
 };
+
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also drains
+// the vector-memory counter, which would expose the latency of the global
+// loads that are deliberately left in flight across stage boundaries.
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
 
 // x / d for 0 <= x < 2^22 and d >= 1, with a float reciprocal and a fix-up.
 __device__ __forceinline__ int fdiv(int x, int d, float inv_d, int &rem)
@@ -359,7 +373,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OCC, OCC)))
         if (tid < 2 * BC) pq_lds[tid] = da0 * (double)chan_const;
     }
     DSQ_STAMP(2);
-    __syncthreads();
+    lds_barrier();
     DSQ_STAMP(3);
 
     for (int cb = 0; cb < NCB - 1; ++cb) {
@@ -370,7 +384,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OCC, OCC)))
 #endif
         compute(std::true_type{}, cur, cb, cb + 1, nxt);
         DSQ_STAMP(4 + 2 * cb);
-        __syncthreads();
+        lds_barrier();
         DSQ_STAMP(5 + 2 * cb);
     }
     compute(std::false_type{}, lds + ((NCB - 1) & 1) * pl.buf_bytes, NCB - 1, 0, nullptr);
@@ -398,7 +412,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OCC, OCC)))
     // channels (128 bytes) of 8 pixels instead of 16 bytes of 32 pixels.
     constexpr int ROWB = 128 + 16;                // staged bytes per pixel (+16: bank spread)
     constexpr int EPI_WAVE = 32 * ROWB + PF * 128;
-    __syncthreads();                              // every wave is done with the patch buffers
+    lds_barrier();                              // every wave is done with the patch buffers
     char *stage = lds + wave * EPI_WAVE;
     int *m_stage = reinterpret_cast<int *>(stage + 32 * ROWB);
 
@@ -560,10 +574,11 @@ hipError_t launch_cfg(const DsqConvArgs &a, const PatchPlan &pl, hipStream_t str
 //   small  128 x  64   waves 4x1, 1 x 2 tiles each  (few pixels: fill the chip)
 //   medium 128 x 128   waves 2x2, 2 x 2
 //   large  256 x 128   waves 2x2, 4 x 2
-struct TileCfg { int WP, WC, PF, CT, UPT; };
-constexpr TileCfg kSmall  = {4, 1, 1, 2, 4};
-constexpr TileCfg kMedium = {2, 2, 2, 2, 4};
-constexpr TileCfg kLarge  = {2, 2, 4, 2, 8};
+struct TileCfg { int WP, WC, PF, CT; };
+constexpr TileCfg kSmall  = {DSQ_S_WP, DSQ_S_WC, DSQ_S_PF, DSQ_S_CT};
+constexpr TileCfg kMedium = {2, 2, 2, 2};
+constexpr TileCfg kLarge  = {2, 2, 4, 2};
+constexpr int kMaxUPT = 12;      // most 16-byte patch units a thread fetches per stage
 
 enum { TILE_SMALL = 0, TILE_MEDIUM = 1, TILE_LARGE = 2 };
 
@@ -600,7 +615,7 @@ bool dsq_conv_patch_supported(const DsqConvArgs &a, int force_tile)
     if ((long long)a.N * a.H * a.W * (a.Cp * dsq_container(a.bits) / 8) > 0x7FFFFFFFLL) return false;
     PatchPlan pl;
     const TileCfg &tc = tile_cfg(force_tile >= 0 ? force_tile : pick_tile(a));
-    return plan_patch(a, 32 * tc.PF * tc.WP, 32 * tc.CT * tc.WC, tc.PF, tc.UPT, kLdsLimit, pl);
+    return plan_patch(a, 32 * tc.PF * tc.WP, 32 * tc.CT * tc.WC, tc.PF, kMaxUPT, kLdsLimit, pl);
 }
 
 hipError_t dsq_launch_conv_patch(const DsqConvArgs &a, int force_tile, hipStream_t stream)
@@ -608,17 +623,25 @@ hipError_t dsq_launch_conv_patch(const DsqConvArgs &a, int force_tile, hipStream
     const int which = force_tile >= 0 ? force_tile : pick_tile(a);
     const TileCfg &tc = tile_cfg(which);
     PatchPlan pl;
-    if (!plan_patch(a, 32 * tc.PF * tc.WP, 32 * tc.CT * tc.WC, tc.PF, tc.UPT, kLdsLimit, pl)) return hipErrorInvalidValue;
+    if (!plan_patch(a, 32 * tc.PF * tc.WP, 32 * tc.CT * tc.WC, tc.PF, kMaxUPT, kLdsLimit, pl)) return hipErrorInvalidValue;
     const int cont = dsq_container(a.bits);
+    const int need = (pl.units + 255) / 256;      // fetch units per thread: instantiated 2, 4, 8, 12
+#define DSQ_TILE(CONT, RR, UPT)                                                                \
+    do {                                                                                       \
+        if (which == TILE_LARGE) return launch_cfg<CONT, RR, 2, 2, 4, 2, UPT, (RR == 3 ? 3 : 1), 2>(a, pl, stream);  \
+        if (which == TILE_MEDIUM) return launch_cfg<CONT, RR, 2, 2, 2, 2, UPT, (RR == 3 ? DSQ_MED_WD : 1), DSQ_MED_OCC>(a, pl, stream); \
+        return launch_cfg<CONT, RR, DSQ_S_WP, DSQ_S_WC, DSQ_S_PF, DSQ_S_CT, UPT, (RR == 3 ? DSQ_SMALL_WD : 1), DSQ_SMALL_OCC>(a, pl, stream); \
+    } while (0)
 #define DSQ_GO(CONT, RR)                                                                       \
     do {                                                                                       \
-        constexpr int WD = RR == 3 ? 3 : 1;                                                    \
-        if (which == TILE_LARGE) return launch_cfg<CONT, RR, 2, 2, 4, 2, 8, WD, 2>(a, pl, stream);  \
-        if (which == TILE_MEDIUM) return launch_cfg<CONT, RR, 2, 2, 2, 2, 4, (RR == 3 ? DSQ_MED_WD : 1), DSQ_MED_OCC>(a, pl, stream); \
-        return launch_cfg<CONT, RR, 4, 1, 1, 2, 4, (RR == 3 ? DSQ_SMALL_WD : 1), DSQ_SMALL_OCC>(a, pl, stream); \
+        if (need <= 2) DSQ_TILE(CONT, RR, 2);                                                  \
+        if (need <= 4) DSQ_TILE(CONT, RR, 4);                                                  \
+        if (need <= 8) DSQ_TILE(CONT, RR, 8);                                                  \
+        DSQ_TILE(CONT, RR, 12);                                                                \
     } while (0)
     if (cont == 4) { if (a.R == 3) DSQ_GO(4, 3); else DSQ_GO(4, 1); }
     else           { if (a.R == 3) DSQ_GO(2, 3); else DSQ_GO(2, 1); }
+#undef DSQ_TILE
 #undef DSQ_GO
     return hipErrorInvalidValue;
 }
