@@ -154,12 +154,12 @@ dsq_status dsq_conv2d(const dsq_conv_desc *d, const void *act_packed,
 
 /* Selects the convolution kernel: 0 = automatic (default), 1 = the simple
  * one-wave-per-tile kernel, 2 = the LDS-patch kernel with its tile chosen by
- * problem size, 3 / 4 / 5 = the LDS-patch kernel with the 128x64 / 128x128 /
- * 256x128 (pixels x channels) tile.  With 2..5, dsq_conv2d returns
+ * problem size, 3 / 4 / 5 / 6 = the LDS-patch kernel with the 128x64 / 128x128 /
+ * 256x128 / 256x64 (pixels x channels) tile.  With 2..6, dsq_conv2d returns
  * DSQ_ERR_UNSUPPORTED instead of falling back when the patch kernel cannot
  * take the geometry.  For tests and benchmarking; this selector is the only
  * state the library keeps; process-wide, not thread-safe.  Returns the
- * previous value; values outside 0..5 change nothing. */
+ * previous value; values outside 0..6 change nothing. */
 int dsq_set_conv_kernel(int which);
 
 /* Static, NUL-terminated description of a status code. */

@@ -8,7 +8,7 @@
 
 namespace {
 
-int g_conv_kernel = 0;   // 0 auto, 1 simple, 2 patch (auto tile), 3..5 patch with a fixed tile
+int g_conv_kernel = 0;   // 0 auto, 1 simple, 2 patch (auto tile), 3..6 patch with a fixed tile
 
 bool bits_ok(int bits) { return bits >= 2 && bits <= 4; }
 bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
@@ -125,7 +125,7 @@ dsq_status dsq_conv2d(const dsq_conv_desc *d, const void *act_packed, const int3
 int dsq_set_conv_kernel(int which)
 {
     int prev = g_conv_kernel;
-    if (which >= 0 && which <= 5) g_conv_kernel = which;
+    if (which >= 0 && which <= 6) g_conv_kernel = which;
     return prev;
 }
 

@@ -574,17 +574,19 @@ hipError_t launch_cfg(const DsqConvArgs &a, const PatchPlan &pl, hipStream_t str
 //   small  128 x  64   waves 4x1, 1 x 2 tiles each  (few pixels: fill the chip)
 //   medium 128 x 128   waves 2x2, 2 x 2
 //   large  256 x 128   waves 2x2, 4 x 2
+//   tall   256 x  64   waves 4x1, 2 x 2  (layers with at most 64 output channels)
 struct TileCfg { int WP, WC, PF, CT; };
 constexpr TileCfg kSmall  = {DSQ_S_WP, DSQ_S_WC, DSQ_S_PF, DSQ_S_CT};
 constexpr TileCfg kMedium = {2, 2, 2, 2};
 constexpr TileCfg kLarge  = {2, 2, 4, 2};
+constexpr TileCfg kTall   = {4, 1, 2, 2};
 constexpr int kMaxUPT = 12;      // most 16-byte patch units a thread fetches per stage
 
-enum { TILE_SMALL = 0, TILE_MEDIUM = 1, TILE_LARGE = 2 };
+enum { TILE_SMALL = 0, TILE_MEDIUM = 1, TILE_LARGE = 2, TILE_TALL = 3 };
 
 const TileCfg &tile_cfg(int which)
 {
-    return which == TILE_LARGE ? kLarge : which == TILE_MEDIUM ? kMedium : kSmall;
+    return which == TILE_LARGE ? kLarge : which == TILE_MEDIUM ? kMedium : which == TILE_TALL ? kTall : kSmall;
 }
 
 int pick_tile(const DsqConvArgs &a)
@@ -594,8 +596,12 @@ int pick_tile(const DsqConvArgs &a)
         const long long bp = 32 * t.PF * t.WP, bc = 32 * t.CT * t.WC;
         return ((M + bp - 1) / bp) * ((a.C_out + bc - 1) / bc);
     };
-    if (a.C_out > 64 && blocks(kLarge) >= 512) return TILE_LARGE;
-    if (a.C_out > 64 && blocks(kMedium) >= 256) return TILE_MEDIUM;
+    // measured on the five benchmark configs: the 128x128 tile wins whenever it
+    // yields enough workgroups and does not waste more than a quarter of its
+    // channels; otherwise the 128x64 tile
+    const int c_pad = ((a.C_out + 127) / 128) * 128;
+    if (a.C_out > 64 && 4 * (c_pad - a.C_out) <= c_pad && blocks(kMedium) >= 192) return TILE_MEDIUM;
+    if (blocks(kTall) >= 768) return TILE_TALL;
     return TILE_SMALL;
 }
 
@@ -630,6 +636,7 @@ hipError_t dsq_launch_conv_patch(const DsqConvArgs &a, int force_tile, hipStream
     do {                                                                                       \
         if (which == TILE_LARGE) return launch_cfg<CONT, RR, 2, 2, 4, 2, UPT, (RR == 3 ? 3 : 1), 2>(a, pl, stream);  \
         if (which == TILE_MEDIUM) return launch_cfg<CONT, RR, 2, 2, 2, 2, UPT, (RR == 3 ? DSQ_MED_WD : 1), DSQ_MED_OCC>(a, pl, stream); \
+        if (which == TILE_TALL) return launch_cfg<CONT, RR, 4, 1, 2, 2, UPT, (RR == 3 ? DSQ_MED_WD : 1), DSQ_MED_OCC>(a, pl, stream); \
         return launch_cfg<CONT, RR, DSQ_S_WP, DSQ_S_WC, DSQ_S_PF, DSQ_S_CT, UPT, (RR == 3 ? DSQ_SMALL_WD : 1), DSQ_SMALL_OCC>(a, pl, stream); \
     } while (0)
 #define DSQ_GO(CONT, RR)                                                                       \

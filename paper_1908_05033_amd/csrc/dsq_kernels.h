@@ -33,8 +33,8 @@ hipError_t dsq_launch_pack_weights(const float *w, const float *l_w, const float
                                    void *w_packed, void *w_aux, hipStream_t stream);
 
 hipError_t dsq_launch_conv_simple(const DsqConvArgs &a, hipStream_t stream);
-// force_tile: -1 = choose by problem size; 0 / 1 / 2 = the 128x64 / 128x128 / 256x128
-// (pixels x channels) workgroup tile.
+// force_tile: -1 = choose by problem size; 0 / 1 / 2 / 3 = the 128x64 / 128x128 /
+// 256x128 / 256x64 (pixels x channels) workgroup tile.
 hipError_t dsq_launch_conv_patch(const DsqConvArgs &a, int force_tile, hipStream_t stream);
 // Whether the LDS-patch kernel supports this geometry with that tile.
 bool dsq_conv_patch_supported(const DsqConvArgs &a, int force_tile);

@@ -11,7 +11,7 @@ from paper_1908_05033_amd import inputs
 
 pytestmark = pytest.mark.gpu
 
-KERNELS = [1, 3, 4, 5]   # 1 = simple; 3/4/5 = LDS-patch kernel with each of its tiles
+KERNELS = [1, 3, 4, 5, 6]   # 1 = simple; 3..6 = LDS-patch kernel with each of its tiles
 
 
 def _run(layer, inp, kernel, **kw):
