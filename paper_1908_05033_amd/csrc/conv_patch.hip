@@ -33,24 +33,6 @@
 
 namespace {
 
-#ifndef DSQ_MED_WD
-#define DSQ_MED_WD 3
-#define DSQ_MED_OCC 3
-#endif
-#ifndef DSQ_S_WP
-#define DSQ_S_WP 4
-#define DSQ_S_WC 1
-#define DSQ_S_PF 1
-#define DSQ_S_CT 2
-#endif
-#ifndef DSQ_SMALL_WD
-#define DSQ_SMALL_WD 3
-#define DSQ_SMALL_OCC 3
-#endif
-#ifndef DSQ_STORE_TAP
-#define DSQ_STORE_TAP (WD == T ? T - 1 : T / 2)
-#endif
-
 constexpr int PIX_STRIDE = 80;   // LDS bytes per patch pixel (64 used)
 
 #ifdef DSQ_TRACE
@@ -58,7 +40,7 @@ constexpr int PIX_STRIDE = 80;   // LDS bytes per patch pixel (64 used)
 __device__ unsigned long long dsq_trace_buf[4096 * 16];
 #define DSQ_STAMP(slot)                                                              \
     do {                                                                             \
-        if (lane == 0 && blk_y == 0 && blk_x < 1024 && (slot) < 16)                  \
+        if (lane == 0 && grp == 0 && blk_y == 0 && blk_x < 1024 && (slot) < 16)      \
             dsq_trace_buf[(blk_x * 4 + wave) * 16 + (slot)] = __builtin_amdgcn_s_memtime(); \
     } while (0)
 #else
@@ -111,8 +93,8 @@ __device__ __noinline__ void store4_general(const DsqConvArgs &a, int m, int o0,
     dsq_store4(a, px, m, o0, acc, delta_a);
 }
 
-template <int CONT, int R, int WP, int WC, int PF, int CT, int UPT, int WD, int OCC>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OCC, OCC))) void conv_patch_kernel(DsqConvArgs a, PatchPlan pl)
+template <int CONT, int R, int WP, int WC, int PF, int CT, int UPT, int WD, int OCC, int KS>
+__global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, OCC))) void conv_patch_kernel(DsqConvArgs a, PatchPlan pl)
 {
     constexpr int T = R * R;
     constexpr int UPP = CONT == 4 ? 2 : 1;        // 16-byte fetch units per patch pixel
@@ -130,9 +112,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OCC, OCC)))
     double *pq_lds = reinterpret_cast<double *>(lds + pl.aux_off);
     int *pix_lds = reinterpret_cast<int *>(pq_lds + 2 * BC);
 
-    const int tid = threadIdx.x;
+    // KS = 2: two groups of four waves work on alternating 64-channel blocks of K
+    // (each with its own patch buffers) and add their accumulators at the end, so
+    // that every SIMD hosts two waves whose MFMA and VALU phases can overlap even
+    // when the layer yields only one workgroup per CU.
+    static_assert(KS == 1 || KS == 2, "one or two wave groups");
+    const int tid = threadIdx.x & 255;                 // thread index inside its wave group
     const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int grp = KS == 1 ? 0 : __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 8);
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave index inside the group
     const int col = lane & 31, h = lane >> 5;
     const int wp = wave % WP, wc = wave / WP;
 
@@ -180,10 +168,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OCC, OCC)))
                         ((((size_t)(ct0 + c) * NCB + cb) * T + t) * 64) * WLANE + lane_woff;
         wreg[c][t % WD] = *reinterpret_cast<const wpack_t *>(p);
     };
+    // (a group whose first channel block does not exist fetches block 0 and never uses it)
+    const int cb_first = grp < NCB ? grp : 0;
 #pragma unroll
     for (int c = 0; c < CT; ++c)
 #pragma unroll
-        for (int t = 0; t < WD; ++t) fetch_weight(c, t, 0);
+        for (int t = 0; t < WD; ++t) fetch_weight(c, t, cb_first);
 
     DSQ_STAMP(10);
 
@@ -256,7 +246,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OCC, OCC)))
             }
         }
     };
-    fetch_patch(0);
+    fetch_patch(cb_first);
     DSQ_STAMP(13);
     // side tables, needed only after the main loop: the pixels' code sums and the
     // per-channel dequantization constants of this workgroup's channels
@@ -264,7 +254,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OCC, OCC)))
 #pragma unroll
     for (int k = 0; k < UPT; ++k) pix_val[k] = a.pix_sum[src_pix[k]];
     float chan_const = 0.f;
-    if (tid < 2 * BC) {
+    if (grp == 0 && tid < 2 * BC) {
         const int o = blk_y * BC + (tid < BC ? tid : tid - BC);      // < Cop by construction
         chan_const = tid < BC ? a.delta_w[o] : a.l_w[o];
     }
@@ -333,10 +323,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OCC, OCC)))
                     wf[c][0] = dsq_unpack2((uint32_t)wr[0]);
                     wf[c][1] = dsq_unpack2((uint32_t)wr[1]);
                 }
-#ifndef DSQ_DBG_NO_WEIGHT_REFILL
                 if (t + WD < T) fetch_weight(c, t + WD, cur_cb);
                 else if (HAS_NEXT) fetch_weight(c, t + WD - T, next_cb);
-#endif
             }
             // consecutive MFMAs go to different accumulators
 #pragma unroll
@@ -344,24 +332,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OCC, OCC)))
 #pragma unroll
                 for (int c = 0; c < CT; ++c)
 #pragma unroll
-                    for (int f = 0; f < PF; ++f) {
-#ifndef DSQ_DBG_NO_MFMA
+                    for (int f = 0; f < PF; ++f)
                         acc[f][c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[c][kh], af[t & 1][f][kh], acc[f][c], 0, 0, 0);
-#else
-                        acc[f][c][0] += wf[c][kh][0] + af[t & 1][f][kh][0];
-#endif
-                    }
             // half way through the taps the next stage's patch has arrived:
             // unpack it into the other buffer while the matrix cores are busy
-#ifndef DSQ_DBG_NO_PATCH_REFILL
-            if (HAS_NEXT && t == DSQ_STORE_TAP) store_patch(nextbuf);
-#endif
+            if (HAS_NEXT && t == (T / 2)) store_patch(nextbuf);
         }
     };
 
+    // patch buffers: [parity][group]
+    auto patch_buf = [&](int parity) { return lds + (parity * KS + grp) * pl.buf_bytes; };
     DSQ_STAMP(1);
-    store_patch(lds);
-    {
+    store_patch(patch_buf(0));
+    if (grp == 0) {
         int pp = UPP == 2 ? (tid >> 1) : tid;
 #pragma unroll
         for (int k = 0; k < UPT; ++k) {
@@ -376,18 +359,22 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OCC, OCC)))
     lds_barrier();
     DSQ_STAMP(3);
 
-    for (int cb = 0; cb < NCB - 1; ++cb) {
-        char *cur = lds + (cb & 1) * pl.buf_bytes;
-        char *nxt = lds + ((cb + 1) & 1) * pl.buf_bytes;
-#ifndef DSQ_DBG_NO_PATCH_REFILL
-        fetch_patch(cb + 1);
-#endif
-        compute(std::true_type{}, cur, cb, cb + 1, nxt);
-        DSQ_STAMP(4 + 2 * cb);
-        lds_barrier();
-        DSQ_STAMP(5 + 2 * cb);
+    // stage i of this group works on channel block grp + i*KS; all groups take
+    // part in every barrier
+    const int n_iter = (NCB + KS - 1) / KS;
+    for (int i = 0; i < n_iter; ++i) {
+        const int cb = grp + i * KS, nxt_cb = cb + KS;
+        if (cb < NCB) {
+            if (nxt_cb < NCB) {
+                fetch_patch(nxt_cb);
+                compute(std::true_type{}, patch_buf(i & 1), cb, nxt_cb, patch_buf((i + 1) & 1));
+            } else {
+                compute(std::false_type{}, patch_buf(i & 1), cb, 0, nullptr);
+            }
+        }
+        if (i < 7) DSQ_STAMP(4 + i);
+        if (i + 1 < n_iter) lds_barrier();
     }
-    compute(std::false_type{}, lds + ((NCB - 1) & 1) * pl.buf_bytes, NCB - 1, 0, nullptr);
     DSQ_STAMP(14);
 
     // ---- epilogue (see conv_epilogue.h for the algebra) ------------------------
@@ -406,6 +393,20 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OCC, OCC)))
         dsa[f] = (double)sa;
     }
 
+    // Da*Dw and Da*l_w of this lane's channels of one tile: 4 groups of 4
+    auto load_pq = [&](int c, double (&P)[16], double (&Q)[16]) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int ol = (wc * CT + c) * 32 + 8 * q + 4 * h;   // channel inside the workgroup
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { P[4 * q + j] = pq_lds[ol + j]; Q[4 * q + j] = pq_lds[BC + ol + j]; }
+        }
+    };
+    // with two wave groups a wave finishes a single tile: fetch its constants now,
+    // ahead of the exchange of partial sums
+    double P0[16], Q0[16];
+    if (KS == 2 && CT == 2 && fast) load_pq(grp, P0, Q0);
+
     // The results of a 32x32 tile sit in the lanes as [pixel = lane%32][4 groups
     // of 4 channels].  They are staged through this wave's slice of the (now idle)
     // patch buffers so that each store instruction writes the 32 consecutive
@@ -413,7 +414,40 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OCC, OCC)))
     constexpr int ROWB = 128 + 16;                // staged bytes per pixel (+16: bank spread)
     constexpr int EPI_WAVE = 32 * ROWB + PF * 128;
     lds_barrier();                              // every wave is done with the patch buffers
-    char *stage = lds + wave * EPI_WAVE;
+    if (KS == 2) {
+        // each group finishes the channel tiles c with c % 2 == grp: it hands the
+        // partial sums of the other tiles to its partner wave through LDS and adds
+        // the partner's partial sums to its own tiles (integer adds: exact in any
+        // order)
+        static_assert(KS == 1 || CT % 2 == 0, "two wave groups split the channel tiles evenly");
+        char *part = lds + 8 * EPI_WAVE + lane * 16;
+        const int mine = (grp * 4 + wave) * (PF * (CT / 2) * 4096);
+        const int theirs = ((1 - grp) * 4 + wave) * (PF * (CT / 2) * 4096);
+#pragma unroll
+        for (int f = 0; f < PF; ++f)
+#pragma unroll
+            for (int c = 0; c < CT; ++c) {
+                if ((c & 1) == grp) continue;
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    *reinterpret_cast<v4i *>(part + mine + ((f * (CT / 2) + c / 2) * 4 + q) * 1024) =
+                        (v4i){acc[f][c][4 * q], acc[f][c][4 * q + 1], acc[f][c][4 * q + 2], acc[f][c][4 * q + 3]};
+            }
+        lds_barrier();
+#pragma unroll
+        for (int f = 0; f < PF; ++f)
+#pragma unroll
+            for (int c = 0; c < CT; ++c) {
+                if ((c & 1) != grp) continue;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const v4i o4 = *reinterpret_cast<const v4i *>(part + theirs + ((f * (CT / 2) + c / 2) * 4 + q) * 1024);
+                    acc[f][c][4 * q] += o4.x; acc[f][c][4 * q + 1] += o4.y;
+                    acc[f][c][4 * q + 2] += o4.z; acc[f][c][4 * q + 3] += o4.w;
+                }
+            }
+    }
+    char *stage = lds + (grp * 4 + wave) * EPI_WAVE;
     int *m_stage = reinterpret_cast<int *>(stage + 32 * ROWB);
 
     if (fast) {
@@ -423,13 +457,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OCC, OCC)))
         }
 #pragma unroll
         for (int c = 0; c < CT; ++c) {
-            // Da*Dw and Da*l_w of this lane's channels of tile c: 4 groups of 4
+            if (KS == 2 && (c & 1) != grp) continue;
             double P[16], Q[16];
+            if (KS == 2 && CT == 2) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int ol = (wc * CT + c) * 32 + 8 * q + 4 * h;   // channel inside the workgroup
-#pragma unroll
-                for (int j = 0; j < 4; ++j) { P[4 * q + j] = pq_lds[ol + j]; Q[4 * q + j] = pq_lds[BC + ol + j]; }
+                for (int j = 0; j < 16; ++j) { P[j] = P0[j]; Q[j] = Q0[j]; }
+            } else {
+                load_pq(c, P, Q);
             }
             const int o = (ct0 + c) * 32 + (lane & 7) * 4;   // channels this lane stores
 #pragma unroll
@@ -473,7 +507,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OCC, OCC)))
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const int o0 = (ct0 + c) * 32 + 8 * q + 4 * h;
-                    if (o0 < a.C_out)
+                    if (o0 < a.C_out && (KS == 1 || (c & 1) == grp))
                         store4_general(a_copy, m, o0,
                                        (v4i){acc[f][c][4 * q], acc[f][c][4 * q + 1], acc[f][c][4 * q + 2], acc[f][c][4 * q + 3]},
                                        delta_a);
@@ -491,9 +525,10 @@ int plan_lds_bytes(const PatchPlan &p, int BC)
     return p.aux_off + 2 * BC * 8 + p.PR * p.PC * 4;
 }
 
-bool plan_patch(const DsqConvArgs &a, int BP, int BC, int PF, int UPT, int lds_limit, PatchPlan &best)
+bool plan_patch(const DsqConvArgs &a, int BP, int BC, int PF, int CT, int UPT, int lds_limit, int KS, PatchPlan &best)
 {
-    const int epi_bytes = 4 * (32 * (128 + 16) + PF * 128);   // epilogue staging of the four waves
+    // epilogue staging of the four waves (+ the partial sums of a second wave group)
+    const int epi_bytes = 4 * KS * (32 * (128 + 16) + PF * 128) + (KS == 2 ? 8 * PF * (CT / 2) * 4096 : 0);
     const int cont = dsq_container(a.bits);
     const int UPP = cont == 4 ? 2 : 1;
     const int NHo = a.N * a.Ho;
@@ -535,7 +570,7 @@ bool plan_patch(const DsqConvArgs &a, int BP, int BC, int PF, int UPT, int lds_l
         p.inv_PC = 1.0f / (float)p.PC; p.inv_tiles_w = 1.0f / (float)tiles_w;
         p.step_q = (256 / UPP) / p.PC;
         p.step_r = (256 / UPP) % p.PC;
-        p.aux_off = 2 * p.buf_bytes > epi_bytes ? 2 * p.buf_bytes : epi_bytes;
+        p.aux_off = 2 * KS * p.buf_bytes > epi_bytes ? 2 * KS * p.buf_bytes : epi_bytes;
         if (plan_lds_bytes(p, BC) > lds_limit) continue;
         if (p.units > 256 * UPT) continue;
         const long long tiles = (long long)p.tiles_w * p.row_tiles;
@@ -551,12 +586,12 @@ bool plan_patch(const DsqConvArgs &a, int BP, int BC, int PF, int UPT, int lds_l
     return found;
 }
 
-template <int CONT, int R, int WP, int WC, int PF, int CT, int UPT, int WD, int OCC>
+template <int CONT, int R, int WP, int WC, int PF, int CT, int UPT, int WD, int OCC, int KS = 1>
 hipError_t launch_cfg(const DsqConvArgs &a, const PatchPlan &pl, hipStream_t stream)
 {
-    auto kern = conv_patch_kernel<CONT, R, WP, WC, PF, CT, UPT, WD, OCC>;
+    auto kern = conv_patch_kernel<CONT, R, WP, WC, PF, CT, UPT, WD, OCC, KS>;
     const int BC = 32 * CT * WC;
-    const size_t lds = (size_t)plan_lds_bytes(pl, BC);
+    const size_t lds = (size_t)plan_lds_bytes(pl, BC);      // pl.aux_off already accounts for KS
     if (lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
@@ -566,7 +601,7 @@ hipError_t launch_cfg(const DsqConvArgs &a, const PatchPlan &pl, hipStream_t str
     p2.inv_tiles_c = 1.0f / (float)p2.tiles_c;
     p2.total_blocks = pl.tiles_w * pl.row_tiles * p2.tiles_c;
     p2.xcd_chunk = (p2.total_blocks + 7) / 8;
-    kern<<<dim3(8 * p2.xcd_chunk), 256, lds, stream>>>(a, p2);
+    kern<<<dim3(8 * p2.xcd_chunk), 256 * KS, lds, stream>>>(a, p2);
     return hipGetLastError();
 }
 
@@ -576,7 +611,7 @@ hipError_t launch_cfg(const DsqConvArgs &a, const PatchPlan &pl, hipStream_t str
 //   large  256 x 128   waves 2x2, 4 x 2
 //   tall   256 x  64   waves 4x1, 2 x 2  (layers with at most 64 output channels)
 struct TileCfg { int WP, WC, PF, CT; };
-constexpr TileCfg kSmall  = {DSQ_S_WP, DSQ_S_WC, DSQ_S_PF, DSQ_S_CT};
+constexpr TileCfg kSmall  = {4, 1, 1, 2};
 constexpr TileCfg kMedium = {2, 2, 2, 2};
 constexpr TileCfg kLarge  = {2, 2, 4, 2};
 constexpr TileCfg kTall   = {4, 1, 2, 2};
@@ -616,28 +651,47 @@ extern "C" int dsq_trace_read(unsigned long long *host, size_t n)
 }
 #endif
 
-bool dsq_conv_patch_supported(const DsqConvArgs &a, int force_tile)
+namespace {
+
+// Tile, wave-group count and plan for a layer.  Two wave groups (K split inside
+// the workgroup) only pay when the layer yields about one workgroup per CU.
+bool choose_plan(const DsqConvArgs &a, int force_tile, int &which, int &ks, PatchPlan &pl)
 {
     if ((long long)a.N * a.H * a.W * (a.Cp * dsq_container(a.bits) / 8) > 0x7FFFFFFFLL) return false;
+    which = force_tile >= 0 ? force_tile : pick_tile(a);
+    const TileCfg &tc = tile_cfg(which);
+    const int BP = 32 * tc.PF * tc.WP, BC = 32 * tc.CT * tc.WC;
+    const long long M = (long long)a.N * a.Ho * a.Wo;
+    const long long blocks = ((M + BP - 1) / BP) * ((a.C_out + BC - 1) / BC);
+    ks = (which == TILE_SMALL && a.Cp >= 128 && blocks <= 320) ? 2 : 1;
+    if (ks == 2 && plan_patch(a, BP, BC, tc.PF, tc.CT, kMaxUPT, kLdsLimit, 2, pl)) return true;
+    ks = 1;
+    return plan_patch(a, BP, BC, tc.PF, tc.CT, kMaxUPT, kLdsLimit, 1, pl);
+}
+
+}  // namespace
+
+bool dsq_conv_patch_supported(const DsqConvArgs &a, int force_tile)
+{
+    int which, ks;
     PatchPlan pl;
-    const TileCfg &tc = tile_cfg(force_tile >= 0 ? force_tile : pick_tile(a));
-    return plan_patch(a, 32 * tc.PF * tc.WP, 32 * tc.CT * tc.WC, tc.PF, kMaxUPT, kLdsLimit, pl);
+    return choose_plan(a, force_tile, which, ks, pl);
 }
 
 hipError_t dsq_launch_conv_patch(const DsqConvArgs &a, int force_tile, hipStream_t stream)
 {
-    const int which = force_tile >= 0 ? force_tile : pick_tile(a);
-    const TileCfg &tc = tile_cfg(which);
+    int which, ks;
     PatchPlan pl;
-    if (!plan_patch(a, 32 * tc.PF * tc.WP, 32 * tc.CT * tc.WC, tc.PF, kMaxUPT, kLdsLimit, pl)) return hipErrorInvalidValue;
+    if (!choose_plan(a, force_tile, which, ks, pl)) return hipErrorInvalidValue;
     const int cont = dsq_container(a.bits);
     const int need = (pl.units + 255) / 256;      // fetch units per thread: instantiated 2, 4, 8, 12
 #define DSQ_TILE(CONT, RR, UPT)                                                                \
     do {                                                                                       \
         if (which == TILE_LARGE) return launch_cfg<CONT, RR, 2, 2, 4, 2, UPT, (RR == 3 ? 3 : 1), 2>(a, pl, stream);  \
-        if (which == TILE_MEDIUM) return launch_cfg<CONT, RR, 2, 2, 2, 2, UPT, (RR == 3 ? DSQ_MED_WD : 1), DSQ_MED_OCC>(a, pl, stream); \
-        if (which == TILE_TALL) return launch_cfg<CONT, RR, 4, 1, 2, 2, UPT, (RR == 3 ? DSQ_MED_WD : 1), DSQ_MED_OCC>(a, pl, stream); \
-        return launch_cfg<CONT, RR, DSQ_S_WP, DSQ_S_WC, DSQ_S_PF, DSQ_S_CT, UPT, (RR == 3 ? DSQ_SMALL_WD : 1), DSQ_SMALL_OCC>(a, pl, stream); \
+        if (which == TILE_MEDIUM) return launch_cfg<CONT, RR, 2, 2, 2, 2, UPT, (RR == 3 ? 3 : 1), 3>(a, pl, stream); \
+        if (which == TILE_TALL) return launch_cfg<CONT, RR, 4, 1, 2, 2, UPT, (RR == 3 ? 3 : 1), 3>(a, pl, stream); \
+        if (ks == 2) return launch_cfg<CONT, RR, 4, 1, 1, 2, UPT, (RR == 3 ? 3 : 1), 2, 2>(a, pl, stream); \
+        return launch_cfg<CONT, RR, 4, 1, 1, 2, UPT, (RR == 3 ? 3 : 1), 3>(a, pl, stream); \
     } while (0)
 #define DSQ_GO(CONT, RR)                                                                       \
     do {                                                                                       \

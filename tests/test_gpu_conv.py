@@ -23,6 +23,16 @@ def _run(layer, inp, kernel, **kw):
         raise
 
 
+@pytest.mark.parametrize("kernel", [3, 4, 5, 6])
+@pytest.mark.parametrize("cfg", [1, 2])
+def test_patch_kernel_takes_the_benchmark_shapes(cfg, kernel):
+    """The tuned kernel (every tile) must accept configs 1 and 2 itself rather
+    than hand them to the fallback: a planner regression would otherwise only
+    show up as skipped tests."""
+    layer, inp = inputs.make_config_layer(cfg)
+    run_layer_gpu(layer, inp, kernel=kernel, with_acc=False)
+
+
 def _check_full(layer, inp, kernel, w_codes=None, **kw):
     got = _run(layer, inp, kernel, w_codes=w_codes, **kw)
     a_code, w_code = oracle_layer(layer, inp, w_codes)
@@ -51,6 +61,11 @@ SMALL = [  # N, C_in, H, W, C_out, R, stride, pad
     (5, 70, 7, 7, 33, 3, 1, 1),
     (1, 320, 7, 7, 300, 1, 1, 0),
     (1, 64, 3, 3, 16, 3, 1, 2),
+    (1, 64, 4, 150, 32, 3, 1, 1),      # wide rows: several column strips with a ragged last one
+    (2, 64, 13, 37, 64, 3, 2, 1),      # stride 2 on odd sizes
+    (3, 128, 1, 1, 48, 1, 1, 0),       # a single pixel per image
+    (1, 3, 12, 12, 8, 3, 1, 1),        # fewer channels than one packed word
+    (1, 64, 2, 300, 16, 1, 2, 0),      # 1x1 stride 2, very wide
 ]
 
 
