@@ -359,22 +359,21 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
     lds_barrier();
     DSQ_STAMP(3);
 
-    // stage i of this group works on channel block grp + i*KS; all groups take
-    // part in every barrier
-    const int n_iter = (NCB + KS - 1) / KS;
-    for (int i = 0; i < n_iter; ++i) {
-        const int cb = grp + i * KS, nxt_cb = cb + KS;
-        if (cb < NCB) {
-            if (nxt_cb < NCB) {
-                fetch_patch(nxt_cb);
-                compute(std::true_type{}, patch_buf(i & 1), cb, nxt_cb, patch_buf((i + 1) & 1));
-            } else {
-                compute(std::false_type{}, patch_buf(i & 1), cb, 0, nullptr);
-            }
-        }
+    // stage i of this group works on channel block grp + i*KS.  Stages that have a
+    // successor prefetch it; the last stage of a group is peeled off the loop.
+    const int n_iter = (NCB + KS - 1) / KS;                  // stages of group 0
+    const int n_full = (NCB - 1 - grp) / KS;                 // stages of this group with a successor
+    for (int i = 0; i < n_full; ++i) {
+        const int cb = grp + i * KS;
+        fetch_patch(cb + KS);
+        compute(std::true_type{}, patch_buf(i & 1), cb, cb + KS, patch_buf((i + 1) & 1));
         if (i < 7) DSQ_STAMP(4 + i);
-        if (i + 1 < n_iter) lds_barrier();
+        lds_barrier();
     }
+    if (grp + n_full * KS < NCB) compute(std::false_type{}, patch_buf(n_full & 1), grp + n_full * KS, 0, nullptr);
+    // every wave of the workgroup takes part in n_iter - 1 stage barriers
+    if (KS > 1)
+        for (int i = n_full; i < n_iter - 1; ++i) lds_barrier();
     DSQ_STAMP(14);
 
     // ---- epilogue (see conv_epilogue.h for the algebra) ------------------------
