@@ -8,7 +8,10 @@ dsq_pack_weights runs once per layer when a model is loaded; it is timed
 separately and is not part of the step.  The workload is the 3x3, 256->256,
 14x14, batch-32, 4-bit layer (the ResNet stage-3 shape).  Inputs live in HBM
 before the timed region; the steps rotate over enough buffer sets that the
-working set exceeds the 256 MB last-level cache.
+working set exceeds the 256 MB last-level cache.  By default the steps are dealt
+to four streams (four batches in flight, each running its own quantize -> conv
+in order), which is how a server with several requests in flight drives the
+library; --serial runs them strictly one after the other and is reported too.
 
 Prints ONE JSON line:  value = effective int-TOPS = 2*MACs*steps / time.
 """
@@ -39,6 +42,9 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--serial", action="store_true", help="no overlap between steps of different batches")
     ap.add_argument("--sets", type=int, default=0, help="buffer sets to rotate over (0 = auto)")
+    ap.add_argument("--streams", type=int, default=4,
+                    help="run the steps as this many independent serial chains, one stream each "
+                         "(0 = the two-stream pipeline: quantize of batch i+1 beside conv of batch i)")
     return ap.parse_args()
 
 
@@ -132,6 +138,23 @@ def main():
             stream.wait_stream(side)
         return g
 
+    def capture_chains(n_chains):
+        """The steps dealt round-robin to n_chains streams; each stream runs its
+        steps (quantize then conv of one batch) strictly in order, the streams run
+        side by side, the way a server keeps several requests in flight."""
+        chains = [torch.cuda.Stream() for _ in range(n_chains)]
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=stream):
+            for c, st in enumerate(chains):
+                st.wait_stream(stream)
+                with torch.cuda.stream(st):
+                    for b in bufs[c::n_chains]:
+                        quant(b)
+                        conv(b)
+            for st in chains:
+                stream.wait_stream(st)
+        return g
+
     def timed_replays(g, n):
         """n replays of a graph between two events on the launch stream."""
         with torch.cuda.stream(stream):
@@ -162,7 +185,12 @@ def main():
         conv(b)
 
     g_step, g_quant, g_conv = capture(step), capture(quant), capture(conv)
-    g_pipe = capture_pipelined() if not args.serial else g_step
+    if args.serial:
+        g_pipe = g_step
+    elif args.streams > 0:
+        g_pipe = capture_chains(args.streams)
+    else:
+        g_pipe = capture_pipelined()
 
     # ---- the timed region: exactly `steps` steps ---------------------------
     n_warm = max(1, -(-args.warmup // sets))
@@ -211,6 +239,7 @@ def main():
             "buffer_sets": sets,
             "launch": ("hipGraph of %d steps replayed %d times; " % (sets, n_rep)) +
                       ("steps strictly serial on one stream" if args.serial else
+                       "%d independent chains of serial steps, one stream each" % args.streams if args.streams > 0 else
                        "quantize of batch i+1 overlaps conv of batch i (two streams)"),
         },
         "kernels": {

@@ -31,6 +31,7 @@ def _load():
         lib.dsq_oracle_delta.argtypes = [C.c_float, C.c_float, C.c_int]
         lib.dsq_oracle_quantize.argtypes = [f32p, C.c_size_t, C.c_float, C.c_float, C.c_int, u8p]
         lib.dsq_oracle_quantize_weights.argtypes = [f32p, f32p, f32p, C.c_int, C.c_size_t, C.c_int, u8p]
+        lib.dsq_oracle_affine_relu.argtypes = [f32p, C.c_int, C.c_int, C.c_size_t, f32p, f32p, C.c_int, f32p]
         lib.dsq_oracle_dequantize.argtypes = [u8p, C.c_size_t, C.c_float, C.c_float, C.c_int, f64p]
         lib.dsq_oracle_conv_codes.argtypes = [u8p, u8p] + geom + [i32p]
         lib.dsq_oracle_conv_dequantized.argtypes = [f64p, f64p] + geom + [f32p]
@@ -89,6 +90,26 @@ def quantize_weights(w, lw, uw, bits):
         _ptr(w, C.c_float), _ptr(lw, C.c_float), _ptr(uw, C.c_float),
         w.shape[0], per_ch, bits, _ptr(code, C.c_uint8)), "quantize_weights")
     return code
+
+
+def affine_relu(y, scale, shift, relu):
+    """scale[c]*y + shift[c] (two binary32 roundings), then max(., 0) if relu;
+    y is [N, C, H, W] float32."""
+    y = _arr(y, np.float32)
+    scale, shift = _arr(scale, np.float32), _arr(shift, np.float32)
+    assert y.ndim == 4 and scale.shape == shift.shape == (y.shape[1],)
+    z = np.empty(y.shape, dtype=np.float32)
+    _check(_load().dsq_oracle_affine_relu(
+        _ptr(y, C.c_float), y.shape[0], y.shape[1], y.shape[2] * y.shape[3],
+        _ptr(scale, C.c_float), _ptr(shift, C.c_float), int(bool(relu)), _ptr(z, C.c_float)), "affine_relu")
+    return z
+
+
+def requantize(y, scale, shift, relu, l, u, bits):
+    """Codes of the next layer's input: the layer output y [N, C, H, W] mapped
+    by affine_relu and quantized for the next layer's range [l, u]
+    (Algorithm 1 steps 1 and 3 of the next layer)."""
+    return quantize(affine_relu(y, scale, shift, relu), l, u, bits)
 
 
 def dequantize(code, l, u, bits):

@@ -100,6 +100,32 @@ int dsq_oracle_quantize_weights(const float *w, const float *lw,
     return ORACLE_OK;
 }
 
+/* Between two quantized layers of a deployed network the convolution output o
+ * of Algorithm 1 step 5 passes through the per-channel affine map a folded
+ * batch normalisation leaves behind and, optionally, a ReLU, and is then the
+ * input a of the next layer's Algorithm 1.  In binary32, one rounding per
+ * operation, multiplication first:
+ *     z = y * scale[c];  z = z + shift[c];  z = max(z, 0) if relu
+ * y is N x C x (HW), channel-major inside one image. */
+int dsq_oracle_affine_relu(const float *y, int n_img, int channels, size_t hw,
+                           const float *scale, const float *shift, int relu,
+                           float *z)
+{
+    if (!y || !z || !scale || !shift || n_img <= 0 || channels <= 0) return ORACLE_BAD_ARG;
+    for (int n = 0; n < n_img; ++n)
+        for (int c = 0; c < channels; ++c) {
+            const float *src = y + ((size_t)n * channels + c) * hw;
+            float *dst = z + ((size_t)n * channels + c) * hw;
+            for (size_t i = 0; i < hw; ++i) {
+                float prod = src[i] * scale[c];
+                float v = prod + shift[c];
+                if (relu) v = fmaxf(v, 0.0f);
+                dst[i] = v;
+            }
+        }
+    return ORACLE_OK;
+}
+
 /* Algorithm 1 step 4: value = l + Delta * code, as a real number.  l and
  * Delta are the binary32 numbers; the product and sum are done in double,
  * where they are exact (24-bit x 8-bit + 24-bit significands). */

@@ -2,6 +2,7 @@
 mathematics fix, never against itself or the GPU path."""
 import itertools
 import math
+import os
 from fractions import Fraction
 
 import numpy as np
@@ -304,3 +305,53 @@ def test_accumulator_budget_matches_table1(golden_dir):
 def test_table9_ratio_is_the_claimed_speedup(golden_dir):
     t = dict((k, float(v)) for k, v in _read_table(golden_dir + "/table9_resnet18_ms.txt"))
     assert round(t["ncnn_8bit_ms"] / t["dsq_2bit_ms"], 1) == t["claimed_speedup_upto"]
+
+
+# ---------------------------------------------------------------------------
+# layer-to-layer map (affine + ReLU + next layer's quantizer)
+# ---------------------------------------------------------------------------
+
+def test_affine_relu_hand_derived_roundings(golden_dir):
+    for line in open(os.path.join(golden_dir, "affine_two_roundings.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        y, s, b, relu, want = line.split()
+        got = oracle.affine_relu(np.full((1, 1, 1, 1), float.fromhex(y), np.float32),
+                                 [float.fromhex(s)], [float.fromhex(b)], int(relu))
+        assert got.reshape(()).item() == float.fromhex(want), line
+
+
+def test_affine_relu_is_numpy_float32_arithmetic_per_channel():
+    rng = np.random.default_rng(11)
+    y = rng.standard_normal((3, 5, 4, 7)).astype(np.float32)     # H != W, N > 1
+    s = rng.standard_normal(5).astype(np.float32)
+    b = rng.standard_normal(5).astype(np.float32)
+    want = y * s[None, :, None, None]          # numpy rounds each float32 operation
+    want = want + b[None, :, None, None]
+    assert np.array_equal(oracle.affine_relu(y, s, b, False), want)
+    assert np.array_equal(oracle.affine_relu(y, s, b, True), np.maximum(want, np.float32(0)))
+    # the channel index is axis 1: a one-hot scale leaves exactly that channel
+    for c in range(5):
+        e = np.zeros(5, np.float32)
+        e[c] = 1
+        z = oracle.affine_relu(y, e, np.zeros(5, np.float32), False)
+        assert np.array_equal(z[:, c], y[:, c]) and not z[:, np.arange(5) != c].any()
+
+
+def test_requantize_is_nearest_level_of_the_mapped_value():
+    rng = np.random.default_rng(12)
+    y = (rng.standard_normal((2, 3, 3, 4)) * 2).astype(np.float32)
+    s = np.array([0.5, 1.25, 2.0], np.float32)
+    b = np.array([0.1, -0.2, 0.3], np.float32)
+    l, u, bits = 0.0, 3.0, 3
+    got = oracle.requantize(y, s, b, True, l, u, bits)
+    top = (1 << bits) - 1
+    d = Fraction(float(np.float32(u) - np.float32(l))) / top
+    for idx in np.ndindex(*y.shape):
+        z = np.float32(y[idx] * s[idx[1]]) + b[idx[1]]          # float32 scalars: two roundings
+        z = max(Fraction(float(z)), Fraction(0))
+        z = min(max(z, Fraction(l)), Fraction(u))
+        t = (z - Fraction(l)) / d
+        if abs((t % 1) - Fraction(1, 2)) < Fraction(1, 1000):
+            continue                                             # too close to a midpoint for this check
+        assert got[idx] == int(t + Fraction(1, 2)), idx
