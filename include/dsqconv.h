@@ -152,12 +152,49 @@ dsq_status dsq_conv2d(const dsq_conv_desc *d, const void *act_packed,
                       dsq_layout out_layout, int32_t *acc_or_null,
                       void *hip_stream);
 
+/* ---- dsq_conv2d_requant: one layer chained onto the next -----------------
+ * Alg. 1 steps 4 and 5 of this layer followed by steps 1 and 3 of the layer that
+ * consumes its output (Sec. 3.5 "Training and Deploying": at inference the
+ * network runs on the integer codes from layer to layer).  For every output
+ * element the call evaluates, without writing the float tensor to memory,
+ *     y    = the binary32 value dsq_conv2d would store
+ *     z    = y * scale[o]            (binary32, rounded)
+ *     z    = z + shift[o]            (binary32, rounded)   folded batch norm
+ *     z    = max(z, 0)               if relu != 0
+ *     code = the quantizer at the top of this file applied to z with
+ *            (l_next, u_next, bits_next)
+ * and writes the codes in the packed activation format for C_out channels
+ * ([N][Ho][Wo][C_out rounded up to 64], padding channels hold code 0) plus the
+ * per-pixel code sums: exactly what dsq_quantize_act would have produced from
+ * the NHWC tensor z, ready to be the act_packed / pix_code_sum of the next
+ * dsq_conv2d or dsq_conv2d_requant.
+ *
+ * d .. w_aux        as for dsq_conv2d
+ * scale, shift      device, float32 [C_out], or NULL for 1 and 0
+ * l_next, u_next, bits_next   clip range and width of the next layer's
+ *                   activation quantizer (bits_next may differ from d->bits)
+ * codes_next        device, out, dsq_act_packed_bytes(N, Ho, Wo, C_out,
+ *                   bits_next) bytes; codes_bytes is the caller's buffer size
+ * pix_code_sum_next device, out, int32[N*Ho*Wo]; the call clears it with a fill
+ *                   kernel on the same stream (no memset node, so the call can
+ *                   be captured into a HIP graph) and accumulates with integer
+ *                   atomics, which are exact in any order
+ */
+dsq_status dsq_conv2d_requant(const dsq_conv_desc *d, const void *act_packed,
+                              const int32_t *pix_code_sum, float l_a, float u_a,
+                              const void *w_packed, const void *w_aux,
+                              const float *scale, const float *shift, int relu,
+                              float l_next, float u_next, int bits_next,
+                              void *codes_next, size_t codes_bytes,
+                              int32_t *pix_code_sum_next, void *hip_stream);
+
 /* Selects the convolution kernel: 0 = automatic (default), 1 = the simple
  * one-wave-per-tile kernel, 2 = the LDS-patch kernel with its tile chosen by
  * problem size, 3 / 4 / 5 / 6 = the LDS-patch kernel with the 128x64 / 128x128 /
  * 256x128 / 256x64 (pixels x channels) tile.  With 2..6, dsq_conv2d returns
  * DSQ_ERR_UNSUPPORTED instead of falling back when the patch kernel cannot
- * take the geometry.  For tests and benchmarking; this selector is the only
+ * take the geometry (the 256x128 tile has no dsq_conv2d_requant variant and
+ * reports the same).  For tests and benchmarking; this selector is the only
  * state the library keeps; process-wide, not thread-safe.  Returns the
  * previous value; values outside 0..6 change nothing. */
 int dsq_set_conv_kernel(int which);

@@ -20,7 +20,7 @@ DSQ_OK = 0
 
 EXPORTS = [
     "dsq_act_packed_bytes", "dsq_wgt_packed_bytes", "dsq_wgt_aux_bytes",
-    "dsq_quantize_act", "dsq_pack_weights", "dsq_conv2d",
+    "dsq_quantize_act", "dsq_pack_weights", "dsq_conv2d", "dsq_conv2d_requant",
     "dsq_set_conv_kernel", "dsq_status_string",
 ]
 
@@ -63,6 +63,9 @@ def load_library():
     lib.dsq_pack_weights.argtypes = [vp, vp, vp, vp, i, i, i, i, i, vp, sz, vp, sz, vp]
     lib.dsq_conv2d.restype = i
     lib.dsq_conv2d.argtypes = [C.POINTER(dsq_conv_desc), vp, vp, f, f, vp, vp, vp, i, vp, vp]
+    lib.dsq_conv2d_requant.restype = i
+    lib.dsq_conv2d_requant.argtypes = [C.POINTER(dsq_conv_desc), vp, vp, f, f, vp, vp, vp, vp, i, f, f, i,
+                                       vp, sz, vp, vp]
     lib.dsq_set_conv_kernel.restype = i
     lib.dsq_set_conv_kernel.argtypes = [i]
     lib.dsq_status_string.restype = C.c_char_p
@@ -138,6 +141,18 @@ def dsq_conv2d(desc, act_packed, pix_code_sum, l_a, u_a, w_packed, w_aux, out, o
         _dev_ptr(w_packed, torch.uint8), _dev_ptr(w_aux, torch.uint8),
         _dev_ptr(out, torch.float32), out_layout,
         _dev_ptr(acc_or_none, torch.int32, True), _stream(stream)))
+
+
+def dsq_conv2d_requant(desc, act_packed, pix_code_sum, l_a, u_a, w_packed, w_aux, scale, shift, relu,
+                       l_next, u_next, bits_next, codes_next, pix_code_sum_next, stream=None):
+    _check(load_library().dsq_conv2d_requant(
+        C.byref(desc) if desc is not None else None,
+        _dev_ptr(act_packed, torch.uint8), _dev_ptr(pix_code_sum, torch.int32), l_a, u_a,
+        _dev_ptr(w_packed, torch.uint8), _dev_ptr(w_aux, torch.uint8),
+        _dev_ptr(scale, torch.float32, True), _dev_ptr(shift, torch.float32, True), int(bool(relu)),
+        l_next, u_next, bits_next,
+        _dev_ptr(codes_next, torch.uint8), codes_next.numel() if codes_next is not None else 0,
+        _dev_ptr(pix_code_sum_next, torch.int32), _stream(stream)))
 
 
 def dsq_set_conv_kernel(which):

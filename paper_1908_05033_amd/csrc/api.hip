@@ -75,11 +75,14 @@ dsq_status dsq_pack_weights(const float *w_oihw, const float *l_w, const float *
     return e == hipSuccess ? DSQ_OK : DSQ_ERR_HIP;
 }
 
-dsq_status dsq_conv2d(const dsq_conv_desc *d, const void *act_packed, const int32_t *pix_code_sum,
-                      float l_a, float u_a, const void *w_packed, const void *w_aux, float *out,
-                      dsq_layout out_layout, int32_t *acc_or_null, void *hip_stream)
+namespace {
+
+// Geometry checks shared by the convolution entry points; fills the part of the
+// kernel arguments that does not depend on where the results go.
+dsq_status conv_args(const dsq_conv_desc *d, const void *act_packed, const int32_t *pix_code_sum,
+                     float l_a, float u_a, const void *w_packed, const void *w_aux, DsqConvArgs &a)
 {
-    if (!d || !act_packed || !pix_code_sum || !w_packed || !w_aux || !out) return DSQ_ERR_NULL;
+    if (!d || !act_packed || !pix_code_sum || !w_packed || !w_aux) return DSQ_ERR_NULL;
     if (!bits_ok(d->bits)) return DSQ_ERR_BITS;
     if (!range_ok(l_a, u_a)) return DSQ_ERR_RANGE;
     if (d->N <= 0 || d->C_in <= 0 || d->H <= 0 || d->W <= 0 || d->C_out <= 0 || d->R <= 0 ||
@@ -88,20 +91,17 @@ dsq_status dsq_conv2d(const dsq_conv_desc *d, const void *act_packed, const int3
     if (d->R != d->S || (d->R != 1 && d->R != 3) || (d->stride != 1 && d->stride != 2) ||
         d->pad > d->R - 1)
         return DSQ_ERR_UNSUPPORTED;
-    if (out_layout != DSQ_NHWC && out_layout != DSQ_NCHW) return DSQ_ERR_UNSUPPORTED;
     if (d->H + 2 * d->pad < d->R || d->W + 2 * d->pad < d->S) return DSQ_ERR_SHAPE;
     const int Ho = (d->H + 2 * d->pad - d->R) / d->stride + 1;
     const int Wo = (d->W + 2 * d->pad - d->S) / d->stride + 1;
     if (Ho <= 0 || Wo <= 0) return DSQ_ERR_SHAPE;
     const int Cp = dsq_round_up(d->C_in, 64), Cop = dsq_round_up(d->C_out, 256);
     if ((long long)d->N * d->H * d->W * Cp > kMaxElems) return DSQ_ERR_UNSUPPORTED;
-    if ((long long)d->N * Ho * Wo * d->C_out > kMaxElems) return DSQ_ERR_UNSUPPORTED;
+    if ((long long)d->N * Ho * Wo * dsq_round_up(d->C_out, 64) > kMaxElems) return DSQ_ERR_UNSUPPORTED;
     if ((long long)d->N * Ho * Wo + 1024 > kMaxElems) return DSQ_ERR_UNSUPPORTED;
-    if (!aligned16(act_packed) || !aligned16(pix_code_sum) || !aligned16(w_packed) ||
-        !aligned16(w_aux) || !aligned16(out) || (acc_or_null && !aligned16(acc_or_null)))
+    if (!aligned16(act_packed) || !aligned16(pix_code_sum) || !aligned16(w_packed) || !aligned16(w_aux))
         return DSQ_ERR_ALIGN;
 
-    DsqConvArgs a;
     a.N = d->N; a.C_in = d->C_in; a.H = d->H; a.W = d->W; a.C_out = d->C_out; a.R = d->R;
     a.stride = d->stride; a.pad = d->pad; a.bits = d->bits;
     a.Ho = Ho; a.Wo = Wo; a.Cp = Cp; a.Cop = Cop;
@@ -111,15 +111,64 @@ dsq_status dsq_conv2d(const dsq_conv_desc *d, const void *act_packed, const int3
     a.l_w = a.delta_w + Cop;
     a.sw_total = (const int32_t *)(a.l_w + Cop);
     a.sw_tap = a.sw_total + Cop;
-    a.out = out; a.acc = acc_or_null; a.out_nchw = out_layout == DSQ_NCHW;
+    a.out = nullptr; a.acc = nullptr; a.out_nchw = 0;
+    a.rq = 0; a.rq_scale = nullptr; a.rq_shift = nullptr; a.rq_relu = 0;
+    a.rq_l = 0.f; a.rq_u = 1.f; a.rq_bits = 4; a.rq_Cp = 0; a.rq_codes = nullptr; a.rq_pix = nullptr;
+    return DSQ_OK;
+}
 
+dsq_status launch_conv(const DsqConvArgs &a, hipStream_t stream)
+{
     hipError_t e;
     const int force_tile = g_conv_kernel >= 3 ? g_conv_kernel - 3 : -1;
     const bool patch_ok = g_conv_kernel != 1 && dsq_conv_patch_supported(a, force_tile);
     if (g_conv_kernel >= 2 && !patch_ok) return DSQ_ERR_UNSUPPORTED;
-    if (!patch_ok) e = dsq_launch_conv_simple(a, (hipStream_t)hip_stream);
-    else e = dsq_launch_conv_patch(a, force_tile, (hipStream_t)hip_stream);
+    if (!patch_ok) e = dsq_launch_conv_simple(a, stream);
+    else e = dsq_launch_conv_patch(a, force_tile, stream);
     return e == hipSuccess ? DSQ_OK : DSQ_ERR_HIP;
+}
+
+}  // namespace
+
+dsq_status dsq_conv2d(const dsq_conv_desc *d, const void *act_packed, const int32_t *pix_code_sum,
+                      float l_a, float u_a, const void *w_packed, const void *w_aux, float *out,
+                      dsq_layout out_layout, int32_t *acc_or_null, void *hip_stream)
+{
+    if (!out) return DSQ_ERR_NULL;
+    DsqConvArgs a;
+    const dsq_status st = conv_args(d, act_packed, pix_code_sum, l_a, u_a, w_packed, w_aux, a);
+    if (st != DSQ_OK) return st;
+    if (out_layout != DSQ_NHWC && out_layout != DSQ_NCHW) return DSQ_ERR_UNSUPPORTED;
+    if (!aligned16(out) || (acc_or_null && !aligned16(acc_or_null))) return DSQ_ERR_ALIGN;
+    a.out = out; a.acc = acc_or_null; a.out_nchw = out_layout == DSQ_NCHW;
+    return launch_conv(a, (hipStream_t)hip_stream);
+}
+
+dsq_status dsq_conv2d_requant(const dsq_conv_desc *d, const void *act_packed,
+                              const int32_t *pix_code_sum, float l_a, float u_a,
+                              const void *w_packed, const void *w_aux, const float *scale,
+                              const float *shift, int relu, float l_next, float u_next,
+                              int bits_next, void *codes_next, size_t codes_bytes,
+                              int32_t *pix_code_sum_next, void *hip_stream)
+{
+    if (!codes_next || !pix_code_sum_next) return DSQ_ERR_NULL;
+    DsqConvArgs a;
+    const dsq_status st = conv_args(d, act_packed, pix_code_sum, l_a, u_a, w_packed, w_aux, a);
+    if (st != DSQ_OK) return st;
+    if (!bits_ok(bits_next)) return DSQ_ERR_BITS;
+    if (!range_ok(l_next, u_next)) return DSQ_ERR_RANGE;
+    if (!aligned16(codes_next) || !aligned16(pix_code_sum_next) || (scale && !aligned16(scale)) ||
+        (shift && !aligned16(shift)))
+        return DSQ_ERR_ALIGN;
+    if (codes_bytes < dsq_act_packed_bytes(a.N, a.Ho, a.Wo, a.C_out, bits_next)) return DSQ_ERR_SIZE;
+    a.rq = 1; a.rq_scale = scale; a.rq_shift = shift; a.rq_relu = relu != 0;
+    a.rq_l = l_next; a.rq_u = u_next; a.rq_bits = bits_next;
+    a.rq_Cp = dsq_round_up(a.C_out, 64);
+    a.rq_codes = codes_next; a.rq_pix = pix_code_sum_next;
+    if (dsq_launch_fill_zero(pix_code_sum_next, (size_t)a.N * a.Ho * a.Wo, (hipStream_t)hip_stream) !=
+        hipSuccess)
+        return DSQ_ERR_HIP;
+    return launch_conv(a, (hipStream_t)hip_stream);
 }
 
 int dsq_set_conv_kernel(int which)

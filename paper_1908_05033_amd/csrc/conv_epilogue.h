@@ -46,12 +46,11 @@ __device__ __forceinline__ DsqPixel dsq_pixel_info(const DsqConvArgs &a, int m, 
     return p;
 }
 
-// Stores the results of one lane: one pixel, four consecutive output channels
+// The binary32 results of one lane: one pixel, four consecutive output channels
 // o0..o0+3 (o0 % 4 == 0, o0 + 3 < Cop).
-__device__ __forceinline__ void dsq_store4(const DsqConvArgs &a, const DsqPixel &p, int m, int o0,
-                                           v4i acc, float delta_a)
+__device__ __forceinline__ void dsq_out4(const DsqConvArgs &a, const DsqPixel &p, int o0, v4i acc,
+                                         float delta_a, float (&res)[4])
 {
-    if (!p.valid || o0 >= a.C_out) return;
     const float4 dw = *reinterpret_cast<const float4 *>(a.delta_w + o0);
     const float4 lw = *reinterpret_cast<const float4 *>(a.l_w + o0);
     const float dwv[4] = {dw.x, dw.y, dw.z, dw.w};
@@ -59,7 +58,6 @@ __device__ __forceinline__ void dsq_store4(const DsqConvArgs &a, const DsqPixel 
     const int accv[4] = {acc.x, acc.y, acc.z, acc.w};
     const int T = a.R * a.R;
     const bool full = p.ntaps == T;
-    float res[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const double da = (double)delta_a, dwj = (double)dwv[j], lwj = (double)lwv[j];
@@ -77,6 +75,17 @@ __device__ __forceinline__ void dsq_store4(const DsqConvArgs &a, const DsqPixel 
         }
         res[j] = (float)v;
     }
+}
+
+// Stores the results of one lane: one pixel, four consecutive output channels
+// o0..o0+3 (o0 % 4 == 0, o0 + 3 < Cop).
+__device__ __forceinline__ void dsq_store4(const DsqConvArgs &a, const DsqPixel &p, int m, int o0,
+                                           v4i acc, float delta_a)
+{
+    if (!p.valid || o0 >= a.C_out) return;
+    const int accv[4] = {acc.x, acc.y, acc.z, acc.w};
+    float res[4];
+    dsq_out4(a, p, o0, acc, delta_a, res);
     if (!a.out_nchw) {
         const size_t base = (size_t)m * a.C_out + o0;
         if ((a.C_out & 3) == 0) {
@@ -99,4 +108,86 @@ __device__ __forceinline__ void dsq_store4(const DsqConvArgs &a, const DsqPixel 
                 if (a.acc) a.acc[idx] = accv[j];
             }
     }
+}
+
+// ---- chained mode: the next layer's codes instead of the fp32 tensor --------
+//
+// The next layer's Algorithm 1 steps 1 and 3 applied to this layer's output:
+// z = y*scale[o] + shift[o] (two binary32 roundings), optional ReLU, then the
+// uniform quantizer with the next layer's range.
+
+// Codes of four consecutive channels o0..o0+3 from their fp32 results y and the
+// channels' scale / shift, one code per byte; channels >= C_out give code 0.
+// Adds the codes to `sum`.
+__device__ __forceinline__ uint32_t dsq_requant4(const DsqConvArgs &a, int o0, const float (&y)[4],
+                                                 const float (&sc)[4], const float (&sh)[4],
+                                                 float delta_n, int top_n, int &sum)
+{
+    int c[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        float z = y[j] * sc[j];
+        z = z + sh[j];
+        if (a.rq_relu) z = fmaxf(z, 0.0f);
+        c[j] = o0 + j < a.C_out ? dsq_code(z, a.rq_l, a.rq_u, delta_n, top_n) : 0;
+        sum += c[j];
+    }
+    return dsq_bytes4(c[0], c[1], c[2], c[3]);
+}
+
+// Packs and stores one pixel's 32 channels [o_tile, o_tile + 32) of the next
+// layer's input.  In the accumulator layout of the 32x32x32 matrix instruction
+// lane L (pixel L%32, h = L/32) holds channels o_tile + 8q + 4h + 0..3 for
+// q = 0..3; bytes[q] carries their codes one per byte.  Lanes L and L^32 hold
+// the two halves of every 8-channel word and swap them; the h = 0 lane then
+// stores the 16 (4-bit containers) or 8 (2-bit) bytes of the pixel.  Must be
+// called by all 64 lanes; `m` < 0 marks a lane without a pixel.  Returns the
+// pixel's code sum over these 32 channels (both lanes of the pair get it).
+__device__ __forceinline__ int dsq_requant_store32(const DsqConvArgs &a, int m, int o_tile, int h,
+                                                   const uint32_t (&bytes)[4], int sum)
+{
+    uint32_t other[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) other[q] = (uint32_t)__shfl_xor((int)bytes[q], 32);
+    const int total = sum + __shfl_xor(sum, 32);
+    if (h == 0 && m >= 0 && o_tile < a.rq_Cp) {
+        char *dst = (char *)a.rq_codes;
+        if (dsq_container(a.rq_bits) == 4) {
+            // word q = channels 8q..8q+7: byte j = c[j] | c[j+4] << 4
+            const v4i w = {(int)(bytes[0] | other[0] << 4), (int)(bytes[1] | other[1] << 4),
+                           (int)(bytes[2] | other[2] << 4), (int)(bytes[3] | other[3] << 4)};
+            *reinterpret_cast<v4i *>(dst + ((size_t)m * a.rq_Cp + o_tile) / 2) = w;
+        } else {
+            // word = 16 channels: byte j = c[j] | c[j+4] << 2 | c[j+8] << 4 | c[j+12] << 6
+            const v2i w = {(int)(bytes[0] | other[0] << 2 | bytes[1] << 4 | other[1] << 6),
+                           (int)(bytes[2] | other[2] << 2 | bytes[3] << 4 | other[3] << 6)};
+            *reinterpret_cast<v2i *>(dst + ((size_t)m * a.rq_Cp + o_tile) / 4) = w;
+        }
+    }
+    return total;
+}
+
+// One whole 32-channel tile of one pixel through the general formulas (any
+// l_a, any border).  All 64 lanes must call it.
+__device__ __forceinline__ int dsq_requant_tile(const DsqConvArgs &a, const DsqPixel &px, int m, int o_tile,
+                                                int h, const v16i &acc, float delta_a)
+{
+    const int top_n = (1 << a.rq_bits) - 1;
+    const float delta_n = dsq_delta(a.rq_l, a.rq_u, top_n);
+    uint32_t bytes[4];
+    int sum = 0;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int o0 = o_tile + 8 * q + 4 * h;            // < Cop: the side tables cover it
+        float y[4], sc[4], sh[4];
+        dsq_out4(a, px, o0, (v4i){acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]}, delta_a, y);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const bool in = o0 + j < a.C_out;
+            sc[j] = in && a.rq_scale ? a.rq_scale[o0 + j] : 1.0f;
+            sh[j] = in && a.rq_shift ? a.rq_shift[o0 + j] : 0.0f;
+        }
+        bytes[q] = dsq_requant4(a, o0, y, sc, sh, delta_n, top_n, sum);
+    }
+    return dsq_requant_store32(a, px.valid ? m : -1, o_tile, h, bytes, sum);
 }

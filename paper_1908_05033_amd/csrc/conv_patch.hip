@@ -93,7 +93,9 @@ __device__ __noinline__ void store4_general(const DsqConvArgs &a, int m, int o0,
     dsq_store4(a, px, m, o0, acc, delta_a);
 }
 
-template <int CONT, int R, int WP, int WC, int PF, int CT, int UPT, int WD, int OCC, int KS>
+// RQ selects the chained-mode epilogue at compile time, so that the plain
+// kernels' register allocation is exactly what it is without that mode.
+template <int CONT, int R, int WP, int WC, int PF, int CT, int UPT, int WD, int OCC, int KS, bool RQ>
 __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, OCC))) void conv_patch_kernel(DsqConvArgs a, PatchPlan pl)
 {
     constexpr int T = R * R;
@@ -111,6 +113,8 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
     constexpr int BC = 32 * CT * WC;
     double *pq_lds = reinterpret_cast<double *>(lds + pl.aux_off);
     int *pix_lds = reinterpret_cast<int *>(pq_lds + 2 * BC);
+    // chained mode: scale and shift of the workgroup's channels (16-byte aligned)
+    float *ss_lds = reinterpret_cast<float *>(lds + ((pl.aux_off + 2 * BC * 8 + pl.PR * pl.PC * 4 + 15) & ~15));
 
     // KS = 2: two groups of four waves work on alternating 64-channel blocks of K
     // (each with its own patch buffers) and add their accumulators at the end, so
@@ -258,6 +262,12 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
         const int o = blk_y * BC + (tid < BC ? tid : tid - BC);      // < Cop by construction
         chan_const = tid < BC ? a.delta_w[o] : a.l_w[o];
     }
+    float rq_const = 0.f;
+    if (RQ && grp == 0 && tid < 2 * BC) {
+        const int o = blk_y * BC + (tid < BC ? tid : tid - BC);
+        const float *tab = tid < BC ? a.rq_scale : a.rq_shift;
+        rq_const = tab != nullptr && o < a.C_out ? tab[o] : (tid < BC ? 1.0f : 0.0f);
+    }
 
     // ---- per-lane LDS offsets of the fragments' pixels -----------------------
     // Tile pixels past the end of the strip multiply patch pixel 0 and are
@@ -354,6 +364,7 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
         // Da*Dw[o] and Da*l_w[o] of this workgroup's channels, in binary64
         const double da0 = (double)dsq_delta(a.l_a, a.u_a, (1 << a.bits) - 1);
         if (tid < 2 * BC) pq_lds[tid] = da0 * (double)chan_const;
+        if (RQ && tid < 2 * BC) ss_lds[tid] = rq_const;
     }
     DSQ_STAMP(2);
     lds_barrier();
@@ -367,7 +378,7 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
         const int cb = grp + i * KS;
         fetch_patch(cb + KS);
         compute(std::true_type{}, patch_buf(i & 1), cb, cb + KS, patch_buf((i + 1) & 1));
-        if (i < 7) DSQ_STAMP(4 + i);
+        if (i < 6) DSQ_STAMP(4 + i);
         lds_barrier();
     }
     if (grp + n_full * KS < NCB) compute(std::false_type{}, patch_buf(n_full & 1), grp + n_full * KS, 0, nullptr);
@@ -449,7 +460,49 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
     char *stage = lds + (grp * 4 + wave) * EPI_WAVE;
     int *m_stage = reinterpret_cast<int *>(stage + 32 * ROWB);
 
-    if (fast) {
+    if (RQ) {
+        // chained mode: the next layer's packed codes and pixel code sums instead
+        // of the fp32 tensor (no transposition needed: a lane pair holds whole
+        // 8-channel words of its pixel)
+        int psum[PF];
+#pragma unroll
+        for (int f = 0; f < PF; ++f) psum[f] = 0;
+        // (l_a = 0 here: the host sends chained layers with l_a != 0 to the simple
+        // kernel.  Constants are fetched four channels at a time, right before
+        // their use, to keep the register footprint of this path small.)
+        const int top_n = (1 << a.rq_bits) - 1;
+        const float delta_n = dsq_delta(a.rq_l, a.rq_u, top_n);
+#pragma unroll
+        for (int c = 0; c < CT; ++c) {
+            if (KS == 2 && (c & 1) != grp) continue;
+            const int o_tile = (ct0 + c) * 32;
+            const int ol = (wc * CT + c) * 32 + 4 * h;       // this lane's first channel inside the workgroup
+#pragma unroll
+            for (int f = 0; f < PF; ++f) {
+                uint32_t bytes[4];
+                int sum = 0;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    float y[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        y[j] = (float)__builtin_fma(pq_lds[ol + 8 * q + j], (double)acc[f][c][4 * q + j],
+                                                    pq_lds[BC + ol + 8 * q + j] * dsa[f]);
+                    const float4 s4 = *reinterpret_cast<const float4 *>(ss_lds + ol + 8 * q);
+                    const float4 b4 = *reinterpret_cast<const float4 *>(ss_lds + BC + ol + 8 * q);
+                    const float sc[4] = {s4.x, s4.y, s4.z, s4.w}, sh[4] = {b4.x, b4.y, b4.z, b4.w};
+                    bytes[q] = dsq_requant4(a, o_tile + 8 * q + 4 * h, y, sc, sh, delta_n, top_n, sum);
+                }
+                psum[f] += dsq_requant_store32(a, frag_m[f], o_tile, h, bytes, sum);
+            }
+        }
+        // one integer atomic per pixel and wave (exact in any order)
+        if (h == 0) {
+#pragma unroll
+            for (int f = 0; f < PF; ++f)
+                if (frag_m[f] >= 0) atomicAdd(a.rq_pix + frag_m[f], psum[f]);
+        }
+    } else if (fast) {
         if (h == 0) {
 #pragma unroll
             for (int f = 0; f < PF; ++f) m_stage[f * 32 + col] = frag_m[f];
@@ -521,7 +574,9 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
 // Picks the strip width TW minimising padded work, then patch size.
 int plan_lds_bytes(const PatchPlan &p, int BC)
 {
-    return p.aux_off + 2 * BC * 8 + p.PR * p.PC * 4;
+    // tables behind the buffers: Da*Dw, Da*l_w (binary64), the patch pixels' code
+    // sums, and the chained mode's scale and shift
+    return ((p.aux_off + 2 * BC * 8 + p.PR * p.PC * 4 + 15) & ~15) + 2 * BC * 4;
 }
 
 bool plan_patch(const DsqConvArgs &a, int BP, int BC, int PF, int CT, int UPT, int lds_limit, int KS, PatchPlan &best)
@@ -585,10 +640,10 @@ bool plan_patch(const DsqConvArgs &a, int BP, int BC, int PF, int CT, int UPT, i
     return found;
 }
 
-template <int CONT, int R, int WP, int WC, int PF, int CT, int UPT, int WD, int OCC, int KS = 1>
-hipError_t launch_cfg(const DsqConvArgs &a, const PatchPlan &pl, hipStream_t stream)
+template <int CONT, int R, int WP, int WC, int PF, int CT, int UPT, int WD, int OCC, int KS, bool RQ>
+hipError_t launch_kernel(const DsqConvArgs &a, const PatchPlan &pl, hipStream_t stream)
 {
-    auto kern = conv_patch_kernel<CONT, R, WP, WC, PF, CT, UPT, WD, OCC, KS>;
+    auto kern = conv_patch_kernel<CONT, R, WP, WC, PF, CT, UPT, WD, OCC, KS, RQ>;
     const int BC = 32 * CT * WC;
     const size_t lds = (size_t)plan_lds_bytes(pl, BC);      // pl.aux_off already accounts for KS
     if (lds > 64 * 1024) {
@@ -609,6 +664,13 @@ hipError_t launch_cfg(const DsqConvArgs &a, const PatchPlan &pl, hipStream_t str
 //   medium 128 x 128   waves 2x2, 2 x 2
 //   large  256 x 128   waves 2x2, 4 x 2
 //   tall   256 x  64   waves 4x1, 2 x 2  (layers with at most 64 output channels)
+template <int CONT, int R, int WP, int WC, int PF, int CT, int UPT, int WD, int OCC, int KS = 1>
+hipError_t launch_cfg(const DsqConvArgs &a, const PatchPlan &pl, hipStream_t stream)
+{
+    if (a.rq) return launch_kernel<CONT, R, WP, WC, PF, CT, UPT, WD, OCC, KS, true>(a, pl, stream);
+    return launch_kernel<CONT, R, WP, WC, PF, CT, UPT, WD, OCC, KS, false>(a, pl, stream);
+}
+
 struct TileCfg { int WP, WC, PF, CT; };
 constexpr TileCfg kSmall  = {4, 1, 1, 2};
 constexpr TileCfg kMedium = {2, 2, 2, 2};
@@ -658,6 +720,9 @@ bool choose_plan(const DsqConvArgs &a, int force_tile, int &which, int &ks, Patc
 {
     if ((long long)a.N * a.H * a.W * (a.Cp * dsq_container(a.bits) / 8) > 0x7FFFFFFFLL) return false;
     which = force_tile >= 0 ? force_tile : pick_tile(a);
+    // chained mode: the test-only tile has no variant, and layers with l_a != 0
+    // (border-dependent terms) go to the simple kernel
+    if (a.rq && (which == TILE_LARGE || a.l_a != 0.0f)) return false;
     const TileCfg &tc = tile_cfg(which);
     const int BP = 32 * tc.PF * tc.WP, BC = 32 * tc.CT * tc.WC;
     const long long M = (long long)a.N * a.Ho * a.Wo;
@@ -686,7 +751,7 @@ hipError_t dsq_launch_conv_patch(const DsqConvArgs &a, int force_tile, hipStream
     const int need = (pl.units + 255) / 256;      // fetch units per thread: instantiated 2, 4, 8, 12
 #define DSQ_TILE(CONT, RR, UPT)                                                                \
     do {                                                                                       \
-        if (which == TILE_LARGE) return launch_cfg<CONT, RR, 2, 2, 4, 2, UPT, (RR == 3 ? 3 : 1), 2>(a, pl, stream);  \
+        if (which == TILE_LARGE) return launch_kernel<CONT, RR, 2, 2, 4, 2, UPT, (RR == 3 ? 3 : 1), 2, 1, false>(a, pl, stream);  \
         if (which == TILE_MEDIUM) return launch_cfg<CONT, RR, 2, 2, 2, 2, UPT, (RR == 3 ? 3 : 1), 3>(a, pl, stream); \
         if (which == TILE_TALL) return launch_cfg<CONT, RR, 4, 1, 2, 2, UPT, (RR == 3 ? 3 : 1), 3>(a, pl, stream); \
         if (ks == 2) return launch_cfg<CONT, RR, 4, 1, 1, 2, UPT, (RR == 3 ? 3 : 1), 2, 2>(a, pl, stream); \

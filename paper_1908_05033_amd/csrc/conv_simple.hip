@@ -25,7 +25,7 @@ __global__ __launch_bounds__(256) void conv_simple_kernel(DsqConvArgs a)
     const int M = a.N * a.Ho * a.Wo;
     const int m = blockIdx.x * 32 + col;
     const int ct = blockIdx.y * 4 + wave;
-    if (ct * 32 >= a.C_out) return;
+    if (ct * 32 >= (a.rq ? a.rq_Cp : a.C_out)) return;     // (uniform per wave)
     const int T = a.R * a.R;
     const int NCB = a.Cp / 64;
     const int top = (1 << a.bits) - 1;
@@ -64,6 +64,11 @@ __global__ __launch_bounds__(256) void conv_simple_kernel(DsqConvArgs a)
         }
     }
     const DsqPixel px = dsq_pixel_info(a, m, M);
+    if (a.rq) {
+        const int total = dsq_requant_tile(a, px, m, ct * 32, h, acc, delta_a);
+        if (h == 0 && px.valid) atomicAdd(a.rq_pix + m, total);
+        return;
+    }
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         const v4i part = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
@@ -76,7 +81,7 @@ __global__ __launch_bounds__(256) void conv_simple_kernel(DsqConvArgs a)
 hipError_t dsq_launch_conv_simple(const DsqConvArgs &a, hipStream_t stream)
 {
     const int M = a.N * a.Ho * a.Wo;
-    dim3 grid((M + 31) / 32, (a.C_out + 127) / 128);
+    dim3 grid((M + 31) / 32, ((a.rq ? a.rq_Cp : a.C_out) + 127) / 128);
     if (dsq_container(a.bits) == 4) conv_simple_kernel<4><<<grid, 256, 0, stream>>>(a);
     else conv_simple_kernel<2><<<grid, 256, 0, stream>>>(a);
     return hipGetLastError();

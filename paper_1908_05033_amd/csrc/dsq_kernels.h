@@ -22,6 +22,17 @@ struct DsqConvArgs {
     float *out;
     int32_t *acc;             // may be null
     int out_nchw;
+    // chained mode (dsq_conv2d_requant): instead of out / acc the kernels write
+    // the next layer's packed codes and add to its pixel code sums
+    int rq;                   // 0 = plain fp32 output
+    const float *rq_scale;    // [C_out] or null (= 1)
+    const float *rq_shift;    // [C_out] or null (= 0)
+    int rq_relu;
+    float rq_l, rq_u;         // next layer's clip range
+    int rq_bits;
+    int rq_Cp;                // C_out rounded up to 64
+    void *rq_codes;           // packed codes of the next layer's input
+    int32_t *rq_pix;          // [N*Ho*Wo], cleared before the launch
 };
 
 hipError_t dsq_launch_quantize_act(const float *x, int layout_nchw, int N, int C, int H, int W,
@@ -31,6 +42,9 @@ hipError_t dsq_launch_quantize_act(const float *x, int layout_nchw, int N, int C
 hipError_t dsq_launch_pack_weights(const float *w, const float *l_w, const float *u_w,
                                    const uint8_t *codes, int C_out, int C_in, int R, int bits,
                                    void *w_packed, void *w_aux, hipStream_t stream);
+
+// Sets n int32 words to zero with a kernel (safe inside graph capture).
+hipError_t dsq_launch_fill_zero(int32_t *p, size_t n, hipStream_t stream);
 
 hipError_t dsq_launch_conv_simple(const DsqConvArgs &a, hipStream_t stream);
 // force_tile: -1 = choose by problem size; 0 / 1 / 2 / 3 = the 128x64 / 128x128 /

@@ -221,3 +221,15 @@ def small_random_case(seed, N, C_in, H, W, C_out, R, stride, pad, bits,
         l_w = (-u_w).astype(np.float32)
     return layer, {"x": x, "w": w, "l_a": float(np.float32(l_a)), "u_a": float(np.float32(u_a)),
                    "l_w": l_w, "u_w": u_w}
+
+
+def affine_params(seed, C_out, shift_std=0.3):
+    """Per-channel scale and shift standing in for a folded batch normalisation
+    between two quantized layers: scale in [0.5, 1.5] with a few negative
+    entries, shift ~ N(0, shift_std^2).  float32 numpy arrays."""
+    g = torch.Generator().manual_seed(BASE_SEED + 77 + seed)
+    scale = torch.rand(C_out, generator=g, dtype=torch.float32) + 0.5
+    flip = torch.rand(C_out, generator=g) < 0.1
+    scale = torch.where(flip, -scale, scale)
+    shift = torch.randn(C_out, generator=g, dtype=torch.float32) * shift_std
+    return scale.numpy().astype(np.float32), shift.numpy().astype(np.float32)

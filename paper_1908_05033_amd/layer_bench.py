@@ -1,6 +1,6 @@
 """Per-layer timing of dsq_quantize_act and dsq_conv2d on one GPU.
 
-    python -m paper_1908_05033_amd.layer_bench --cfg 3 [--bits 4] [--kernel 0]
+    python -m paper_1908_05033_amd.layer_bench --cfg 3 [--bits 4] [--kernel 0] [--chained]
 
 For every layer of a config (shapes from :mod:`paper_1908_05033_amd.inputs`)
 it prints one JSON line: kernel time, effective int-TOPS (2*MACs/s, padding taps
@@ -9,6 +9,10 @@ packed weights, pixel sums, fp32 out) and the GB/s they amount to.  Inputs are
 random tensors drawn on the GPU (timing does not depend on the values); launches
 are captured in a hipGraph that rotates over enough buffer sets to exceed the
 256 MB last-level cache, and timed with events on the launch stream.
+
+With --chained it also times dsq_conv2d_requant (the layer's output written as
+the next layer's packed codes) and, for comparison, the two calls it replaces:
+dsq_conv2d to fp32 followed by dsq_quantize_act of that tensor.
 """
 import argparse
 import json
@@ -39,7 +43,7 @@ def _time_graph(fn, bufs, stream, reps):
     return e0.elapsed_time(e1) * 1e-3 / (reps * len(bufs))
 
 
-def bench_layer(L, kernel=0, min_bytes=600e6, max_sets=16, reps=5):
+def bench_layer(L, kernel=0, min_bytes=600e6, max_sets=16, reps=5, chained=False):
     dev = "cuda"
     gen = torch.Generator(device=dev).manual_seed(inputs.BASE_SEED)
     in_bytes = L.N * L.H * L.W * L.C_in * 4
@@ -69,6 +73,23 @@ def bench_layer(L, kernel=0, min_bytes=600e6, max_sets=16, reps=5):
     def conv(b):
         B.dsq_conv2d(b.desc, b.act_packed, b.pix_code_sum, l_a, u_a, wp, aux, b.out, B.DSQ_NHWC, None)
 
+    if chained:
+        scale = torch.rand(L.C_out, device=dev, generator=gen) + 0.5
+        shift = torch.randn(L.C_out, device=dev, generator=gen) * 0.1
+        l_n, u_n = 0.0, 1.0
+        next_bytes = B.dsq_act_packed_bytes(L.N, L.Ho, L.Wo, L.C_out, L.bits)
+        for b in bufs:
+            b.codes_next = torch.empty(next_bytes, dtype=torch.uint8, device=dev)
+            b.pix_next = torch.empty(L.N * L.Ho * L.Wo, dtype=torch.int32, device=dev)
+
+    def conv_chained(b):
+        B.dsq_conv2d_requant(b.desc, b.act_packed, b.pix_code_sum, l_a, u_a, wp, aux, scale, shift, True,
+                             l_n, u_n, L.bits, b.codes_next, b.pix_next)
+
+    def quant_next(b):      # what the chained call saves: quantizing the fp32 output for the next layer
+        B.dsq_quantize_act(b.out, B.DSQ_NHWC, L.N, L.C_out, L.Ho, L.Wo, l_n, u_n, L.bits,
+                           b.codes_next, b.pix_next)
+
     prev = B.dsq_set_conv_kernel(kernel)
     try:
         stream = torch.cuda.Stream()
@@ -76,9 +97,14 @@ def bench_layer(L, kernel=0, min_bytes=600e6, max_sets=16, reps=5):
             for b in bufs:
                 quant(b)
                 conv(b)
+                if chained:
+                    conv_chained(b)
             torch.cuda.synchronize()
         tq = _time_graph(quant, bufs, stream, reps)
         tc = _time_graph(conv, bufs, stream, reps)
+        if chained:
+            tcc = _time_graph(conv_chained, bufs, stream, reps)
+            tqn = _time_graph(quant_next, bufs, stream, reps)
     finally:
         B.dsq_set_conv_kernel(prev)
     # algorithmic conv bytes: packed weights are counted at the packed code width
@@ -87,7 +113,16 @@ def bench_layer(L, kernel=0, min_bytes=600e6, max_sets=16, reps=5):
     conv_bytes = code_bytes + pix_bytes + w_alg + out_bytes
     quant_bytes = in_bytes + code_bytes + pix_bytes
     tops = 2.0 * L.macs / tc / 1e12
-    return {
+    extra = {}
+    if chained:
+        ch_bytes = code_bytes + pix_bytes + w_alg + next_bytes + L.N * L.Ho * L.Wo * 4
+        extra = {
+            "chained_us": round(tcc * 1e6, 2), "chained_TOPS": round(2.0 * L.macs / tcc / 1e12, 1),
+            "chained_alg_MB": round(ch_bytes / 1e6, 2), "chained_GBps": round(ch_bytes / tcc / 1e9, 1),
+            "unchained_us": round((tc + tqn) * 1e6, 2), "quant_next_us": round(tqn * 1e6, 2),
+            "chained_speedup": round((tc + tqn) / tcc, 2),
+        }
+    return {**extra, **{
         "layer": L.name, "bits": L.bits, "count": L.count,
         "gemm_MxNxK": [L.N * L.Ho * L.Wo, L.C_out, L.C_in * L.R * L.S],
         "conv_us": round(tc * 1e6, 2), "conv_TOPS": round(tops, 1),
@@ -97,7 +132,7 @@ def bench_layer(L, kernel=0, min_bytes=600e6, max_sets=16, reps=5):
         "quant_us": round(tq * 1e6, 2), "quant_GBps": round(quant_bytes / tq / 1e9, 1),
         "quant_frac_hbm_peak": round(quant_bytes / tq / 1e9 / HBM_PEAK_GBS, 4),
         "buffer_sets": sets, "w_buffer_bytes": w_bytes,
-    }
+    }}
 
 
 def main():
@@ -106,13 +141,14 @@ def main():
     ap.add_argument("--bits", type=int, default=None)
     ap.add_argument("--kernel", type=int, default=0)
     ap.add_argument("--layer", type=int, default=None)
+    ap.add_argument("--chained", action="store_true")
     a = ap.parse_args()
     layers = inputs.config_layers(a.cfg, a.bits)
     if a.layer is not None:
         layers = [layers[a.layer]]
     tot_t, tot_macs = 0.0, 0
     for L in layers:
-        r = bench_layer(L, kernel=a.kernel)
+        r = bench_layer(L, kernel=a.kernel, chained=a.chained)
         print(json.dumps(r), flush=True)
         tot_t += (r["conv_us"] + r["quant_us"]) * 1e-6 * L.count
         tot_macs += L.macs * L.count

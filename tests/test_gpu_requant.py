@@ -1,0 +1,214 @@
+"""GPU parity of dsq_conv2d_requant (one layer chained onto the next) against
+the oracle: the next layer's codes and pixel code sums.
+
+The codes are integers decided by binary32 arithmetic on both sides (the
+oracle's and the kernel's recipe are the same sequence of binary32 operations
+on the layer output y).  y itself is a binary64 sum rounded once to binary32;
+the two sides add the terms in different orders, so y can differ in its last
+bit about once in 10^6 elements, and a code can only differ where the
+oracle's own value sits within rounding distance of a quantizer midpoint.
+The tests demand equality everywhere else and a difference of at most one
+code at such places."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from helpers import oracle_layer, round_up, unpack_act
+from paper_1908_05033_amd import binding as B
+from paper_1908_05033_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+KERNELS = [1, 3, 4, 5, 6]
+
+
+def run_requant_gpu(layer, inp, scale, shift, relu, l_n, u_n, bits_n, kernel=0, skip_unsupported=True):
+    L = layer
+    buf = B.alloc_layer(L.N, L.C_in, L.H, L.W, L.C_out, L.R, L.S, L.stride, L.pad, L.bits)
+    xd = inp["x"].permute(0, 2, 3, 1).contiguous().cuda()
+    B.dsq_quantize_act(xd, B.DSQ_NHWC, L.N, L.C_in, L.H, L.W, inp["l_a"], inp["u_a"], L.bits,
+                       buf.act_packed, buf.pix_code_sum)
+    lw = torch.from_numpy(np.ascontiguousarray(inp["l_w"])).cuda()
+    uw = torch.from_numpy(np.ascontiguousarray(inp["u_w"])).cuda()
+    B.dsq_pack_weights(inp["w"].contiguous().cuda(), lw, uw, None, L.C_out, L.C_in, L.R, L.S, L.bits,
+                       buf.w_packed, buf.w_aux)
+    codes = torch.full((B.dsq_act_packed_bytes(L.N, L.Ho, L.Wo, L.C_out, bits_n),), 0xEE,
+                       dtype=torch.uint8, device="cuda")
+    pix = torch.full((L.N * L.Ho * L.Wo,), 12345, dtype=torch.int32, device="cuda")
+    sc = torch.from_numpy(scale).cuda() if scale is not None else None
+    sh = torch.from_numpy(shift).cuda() if shift is not None else None
+    prev = B.dsq_set_conv_kernel(kernel)
+    try:
+        B.dsq_conv2d_requant(buf.desc, buf.act_packed, buf.pix_code_sum, inp["l_a"], inp["u_a"],
+                             buf.w_packed, buf.w_aux, sc, sh, relu, l_n, u_n, bits_n, codes, pix)
+    except B.DsqError as e:
+        if skip_unsupported and kernel >= 2 and e.status == 5:
+            pytest.skip("geometry not supported by the patch kernel")
+        raise
+    finally:
+        B.dsq_set_conv_kernel(prev)
+    torch.cuda.synchronize()
+    c = unpack_act(codes.cpu().numpy(), L.N, L.Ho, L.Wo, L.C_out, bits_n)     # [N, Ho, Wo, Cp]
+    return c, pix.cpu().numpy().reshape(L.N, L.Ho, L.Wo), codes, pix, buf
+
+
+def oracle_requant(layer, inp, scale, shift, relu, l_n, u_n, bits_n):
+    a_code, w_code = oracle_layer(layer, inp)
+    y = oracle.conv_real(a_code, inp["l_a"], inp["u_a"], w_code, inp["l_w"], inp["u_w"],
+                         layer.bits, layer.stride, layer.pad)
+    one = np.ones(layer.C_out, np.float32)
+    z = oracle.affine_relu(y, scale if scale is not None else one,
+                           shift if shift is not None else 0 * one, relu)
+    return y, z, oracle.quantize(z, l_n, u_n, bits_n)
+
+
+def assert_codes_match(got_nhwc, want_nchw, z, l_n, u_n, bits_n, C_out):
+    got = got_nhwc[..., :C_out].transpose(0, 3, 1, 2)
+    assert not got_nhwc[..., C_out:].any(), "padding channels must hold code 0"
+    diff = got.astype(np.int32) - want_nchw.astype(np.int32)
+    bad = diff != 0
+    if bad.any():
+        d = (np.float64(np.float32(u_n)) - np.float64(np.float32(l_n))) / ((1 << bits_n) - 1)
+        t = (np.clip(z.astype(np.float64), l_n, u_n) - l_n) / d
+        near = np.abs((t - np.floor(t)) - 0.5) < 1e-4
+        assert not (bad & ~near).any(), "%d codes differ away from a quantizer midpoint" % (bad & ~near).sum()
+        assert np.abs(diff).max() <= 1
+        assert bad.sum() <= max(1, bad.size // 10000)
+    return int(bad.sum())
+
+
+def next_range(z, relu, q=0.98):
+    """Clip range of the next layer from the oracle's own values."""
+    hi = float(np.quantile(z, q))
+    lo = 0.0 if relu else float(np.quantile(z, 1 - q))
+    return float(np.float32(lo)), float(np.float32(max(hi, lo + 0.1)))
+
+
+SMALL = [  # N, C_in, H, W, C_out, R, stride, pad
+    (2, 64, 9, 7, 64, 3, 1, 1),
+    (1, 24, 10, 11, 144, 1, 1, 0),
+    (3, 144, 5, 6, 24, 1, 1, 0),
+    (2, 96, 7, 9, 40, 3, 2, 1),
+    (1, 128, 8, 8, 70, 3, 1, 0),
+    (5, 70, 7, 7, 33, 3, 1, 1),
+    (1, 320, 7, 7, 300, 1, 1, 0),
+    (1, 64, 4, 150, 32, 3, 1, 1),
+    (1, 3, 12, 12, 8, 3, 1, 1),
+    (2, 256, 6, 6, 256, 3, 1, 1),     # several channel blocks: takes the two-wave-group variant
+]
+
+
+@pytest.mark.parametrize("kernel", KERNELS)
+@pytest.mark.parametrize("l_a,relu", [(0.0, True), (-0.4, False)])
+@pytest.mark.parametrize("bits,bits_n", [(4, 4), (2, 2), (3, 4), (4, 2)])
+@pytest.mark.parametrize("geom", SMALL)
+def test_small_geometries(geom, bits, bits_n, l_a, relu, kernel):
+    """l_a = 0 takes the tuned kernel's own chained epilogue; l_a != 0 (terms that
+    depend on which taps lie inside the image) is served by the simple kernel,
+    and the tuned kernel, when forced, must say so instead of computing."""
+    N, Ci, H, W, Co, R, stride, pad = geom
+    layer, inp = inputs.small_random_case(sum(geom) + bits, N, Ci, H, W, Co, R, stride, pad, bits,
+                                          l_a=l_a, u_a=2.1)
+    scale, shift = inputs.affine_params(sum(geom), Co)
+    y, z, _ = oracle_requant(layer, inp, scale, shift, relu, 0.0, 1.0, bits_n)
+    l_n, u_n = next_range(z, relu)
+    want = oracle.quantize(z, l_n, u_n, bits_n)
+    if kernel >= 2 and l_a != 0.0:
+        with pytest.raises(B.DsqError) as e:
+            run_requant_gpu(layer, inp, scale, shift, relu, l_n, u_n, bits_n, kernel, skip_unsupported=False)
+        assert e.value.status == 5
+        return
+    got, pix, *_ = run_requant_gpu(layer, inp, scale, shift, relu, l_n, u_n, bits_n, kernel)
+    assert_codes_match(got, want, z, l_n, u_n, bits_n, Co)
+    # the pixel sums are those of the codes the kernel itself wrote
+    assert np.array_equal(pix, got.astype(np.int64).sum(axis=3))
+
+
+@pytest.mark.parametrize("kernel", [0, 1])
+def test_without_affine_and_two_calls_in_a_row(kernel):
+    """NULL scale/shift mean 1 and 0; a second call into the same buffers must
+    not see the first call's pixel sums."""
+    layer, inp = inputs.small_random_case(5, 2, 64, 8, 8, 96, 3, 1, 1, 4, l_a=0.0, u_a=2.0)
+    y, z, _ = oracle_requant(layer, inp, None, None, True, 0.0, 1.0, 4)
+    l_n, u_n = next_range(z, True)
+    want = oracle.quantize(z, l_n, u_n, 4)
+    got, pix, codes, pixd, buf = run_requant_gpu(layer, inp, None, None, True, l_n, u_n, 4, kernel)
+    assert_codes_match(got, want, z, l_n, u_n, 4, layer.C_out)
+    B.dsq_conv2d_requant(buf.desc, buf.act_packed, buf.pix_code_sum, inp["l_a"], inp["u_a"],
+                         buf.w_packed, buf.w_aux, None, None, True, l_n, u_n, 4, codes, pixd)
+    torch.cuda.synchronize()
+    assert np.array_equal(pixd.cpu().numpy().reshape(pix.shape), pix)
+
+
+def test_chain_of_two_layers_matches_the_oracle_chain():
+    """Layer A (3x3, chained output) feeds layer B (1x1, fp32 output) without
+    the activation ever being stored as floats; the oracle runs the same two
+    layers from its own codes."""
+    from helpers import assert_out_close
+    la, ia = inputs.small_random_case(21, 2, 64, 12, 10, 96, 3, 1, 1, 4, l_a=0.0, u_a=2.2)
+    scale, shift = inputs.affine_params(21, la.C_out)
+    y, z, _ = oracle_requant(la, ia, scale, shift, True, 0.0, 1.0, 4)
+    l_n, u_n = next_range(z, True)
+    codes_b = oracle.quantize(z, l_n, u_n, 4)                              # [N, 96, Ho, Wo]
+    got, pix, codes_d, pix_d, _ = run_requant_gpu(la, ia, scale, shift, True, l_n, u_n, 4)
+    assert assert_codes_match(got, codes_b, z, l_n, u_n, 4, la.C_out) == 0, \
+        "this seed has no midpoint case; exact equality expected"
+    lb, ib = inputs.small_random_case(22, la.N, la.C_out, la.Ho, la.Wo, 48, 1, 1, 0, 4)
+    w_code = oracle.quantize_weights(ib["w"].numpy(), ib["l_w"], ib["u_w"], 4)
+    ref = oracle.conv_real(codes_b, l_n, u_n, w_code, ib["l_w"], ib["u_w"], 4, 1, 0)
+    buf = B.alloc_layer(lb.N, lb.C_in, lb.H, lb.W, lb.C_out, 1, 1, 1, 0, 4)
+    B.dsq_pack_weights(ib["w"].contiguous().cuda(), torch.from_numpy(ib["l_w"]).cuda(),
+                       torch.from_numpy(ib["u_w"]).cuda(), None, lb.C_out, lb.C_in, 1, 1, 4,
+                       buf.w_packed, buf.w_aux)
+    B.dsq_conv2d(buf.desc, codes_d, pix_d, l_n, u_n, buf.w_packed, buf.w_aux, buf.out, B.DSQ_NHWC, None)
+    torch.cuda.synchronize()
+    dw = [oracle.delta(float(a), float(b), 4) for a, b in zip(ib["l_w"], ib["u_w"])]
+    assert_out_close(buf.out.cpu().numpy().transpose(0, 3, 1, 2), ref, oracle.delta(l_n, u_n, 4), dw)
+
+
+@pytest.mark.parametrize("cfg,layer_index,bits", [(2, 0, 4), (3, 0, 4), (5, 4, 2)])
+def test_full_size_layers_sampled(cfg, layer_index, bits):
+    """Full benchmark shapes in the automatic launch configuration: codes at
+    sampled positions against the oracle's single-output routine; pixel sums
+    against the kernel's own codes everywhere."""
+    layer, inp = inputs.make_config_layer(cfg, layer_index, bits)
+    L = layer
+    scale, shift = inputs.affine_params(cfg, L.C_out, shift_std=0.05)
+    a_code, w_code = oracle_layer(layer, inp)
+    rng = np.random.default_rng(cfg)
+    total = L.N * L.C_out * L.Ho * L.Wo
+    idx = np.unique(np.concatenate([rng.integers(0, total, 3000), [0, total - 1]]))
+    vals, _ = oracle.conv_at(a_code, inp["l_a"], inp["u_a"], w_code, inp["l_w"], inp["u_w"], L.bits,
+                             L.stride, L.pad, idx)
+    o = (idx // (L.Ho * L.Wo)) % L.C_out
+    z = np.float32(vals * scale[o]) + shift[o]           # numpy float32: one rounding per operation
+    z = np.maximum(z, np.float32(0))
+    l_n, u_n = 0.0, float(np.float32(np.quantile(z, 0.98)))
+    want = oracle.quantize(z, l_n, u_n, bits)
+    got, pix, *_ = run_requant_gpu(layer, inp, scale, shift, True, l_n, u_n, bits)
+    n = idx // (L.C_out * L.Ho * L.Wo)
+    oy = (idx // L.Wo) % L.Ho
+    ox = idx % L.Wo
+    g = got[n, oy, ox, o]
+    bad = g != want
+    if bad.any():
+        d = (np.float64(np.float32(u_n)) - l_n) / ((1 << bits) - 1)
+        t = (np.clip(z.astype(np.float64), l_n, u_n) - l_n) / d
+        near = np.abs((t - np.floor(t)) - 0.5) < 1e-4
+        assert not (bad & ~near).any()
+    assert np.array_equal(pix, got.astype(np.int64).sum(axis=3))
+    assert not got[..., L.C_out:].any()
+
+
+def test_argument_errors():
+    layer, inp = inputs.small_random_case(1, 1, 64, 4, 4, 64, 3, 1, 1, 4, l_a=0.0, u_a=2.0)
+    buf = B.alloc_layer(1, 64, 4, 4, 64, 3, 3, 1, 1, 4)
+    codes = torch.empty(B.dsq_act_packed_bytes(1, 4, 4, 64, 4), dtype=torch.uint8, device="cuda")
+    pix = torch.empty(16, dtype=torch.int32, device="cuda")
+    args = (buf.desc, buf.act_packed, buf.pix_code_sum, 0.0, 2.0, buf.w_packed, buf.w_aux, None, None, 1)
+    for tail, status in (((0.0, 1.0, 5, codes, pix), 2), ((1.0, 1.0, 4, codes, pix), 3),
+                         ((0.0, 1.0, 4, codes[:64], pix), 7), ((0.0, 1.0, 4, None, pix), 1)):
+        with pytest.raises(B.DsqError) as e:
+            B.dsq_conv2d_requant(*args, *tail)
+        assert e.value.status == status

@@ -16,7 +16,8 @@ import pytest
 from paper_1908_05033_amd import build as B
 
 CSRC = os.path.join(os.path.dirname(B.__file__), "csrc")
-MAX_SPILLED_VGPRS = 40
+MAX_SPILLED_VGPRS = 40            # whole kernel
+MAX_SCRATCH_IN_MFMA_BLOCK = 32    # scratch instructions in a basic block that issues MFMAs
 
 
 def _device_asm(src):
@@ -36,3 +37,14 @@ def test_kernels_stay_inside_their_register_budget(source):
     assert kernels, "no kernel metadata found in the device assembly"
     over = [(n, int(v), int(s)) for n, v, s in kernels if int(s) > MAX_SPILLED_VGPRS]
     assert not over, "kernels spilling more than %d registers: %s" % (MAX_SPILLED_VGPRS, over[:5])
+    # no variant may spill inside the blocks that feed the matrix cores
+    hot = []
+    for fn in re.split(r"\n(?=_Z\S+:)", asm):
+        name = fn.split(":", 1)[0]
+        for block in re.split(r"\n\.LBB\d+_\d+:", fn):
+            ins = [l.split()[0] for l in block.splitlines() if l.startswith("\t") and not l.startswith("\t.")]
+            if sum("mfma" in i for i in ins) >= 8:
+                n_scratch = sum(i.startswith("scratch_") for i in ins)
+                if n_scratch > MAX_SCRATCH_IN_MFMA_BLOCK:
+                    hot.append((name, n_scratch))
+    assert not hot, "scratch traffic inside MFMA blocks: %s" % hot[:5]
