@@ -45,12 +45,20 @@
  *   Activations: [N][H][W][Cp] with Cp = C rounded up to a multiple of 64,
  *   channels >= C hold code 0; one pixel is Cp*container/8 bytes.
  *   Weights: blocks of 32 output channels x 64 input channels of one filter
- *   tap, ordered [Cop/32][Cp/64][R*S][64 lanes][2 K halves]; lane = 32*h +
- *   (o % 32), and K half kh of that lane holds channels
- *   64*cb + 32*kh + 16*h + 0..15 of output channel o (2 words at 4-bit, 1 word
- *   at 2-bit) -- the operand order of the 32x32x32 int8 matrix instruction.
+ *   tap, ordered [Cop/32][Cp/64][R*S][64 lanes][16 bytes], lane = 32*h + (o % 32).
  *   Cop = C_out rounded up to a multiple of 256; rows >= C_out and channels
- *   >= C_in hold code 0.
+ *   >= C_in hold code 0.  One code per 4-bit field at every width:
+ *     bits 3, 4: the lane's 16 bytes are its two K halves kh = 0, 1, each the
+ *       channels 64*cb + 32*kh + 16*h + 0..15 of output channel o as two words of
+ *       the format above -- the operand order of the 32x32x32 int8 matrix
+ *       instruction;
+ *     bits 2: the lane's 16 bytes are the 32 channels 64*cb + 32*h + 0..31, word d
+ *       (0..3) nibble n (0..7, from the low end) holding channel offset
+ *       16*(d/2) + 4*(d%2) + 8*(n%2) + n/2.  A 2-bit code zero-extended to four
+ *       bits is the FP4 (e2m1) encoding of code/2, so these words are operands
+ *       of the 32x32x64 FP4 matrix instruction as they stand; the nibble order
+ *       is the one in which a packed 2-bit activation word w spreads into
+ *       w & 0x33333333 and (w >> 2) & 0x33333333.
  */
 #ifndef DSQCONV_H
 #define DSQCONV_H

@@ -28,8 +28,8 @@ size_t dsq_act_packed_bytes(int N, int H, int W, int C, int bits)
 size_t dsq_wgt_packed_bytes(int C_out, int C_in, int R, int S, int bits)
 {
     if (C_out <= 0 || C_in <= 0 || R <= 0 || S <= 0 || !bits_ok(bits)) return 0;
-    return (size_t)dsq_round_up(C_out, 256) * R * S *
-           (size_t)(dsq_round_up(C_in, 64) * dsq_container(bits) / 8);
+    // one code per 4-bit field at every width (2-bit layers feed the FP4 matrix instruction)
+    return (size_t)dsq_round_up(C_out, 256) * R * S * (size_t)(dsq_round_up(C_in, 64) / 2);
 }
 
 size_t dsq_wgt_aux_bytes(int C_out, int R, int S)

@@ -33,15 +33,19 @@
 
 namespace {
 
-constexpr int PIX_STRIDE = 80;   // LDS bytes per patch pixel (64 used)
+// LDS bytes per patch pixel: 64 int8 (4-bit containers) or 32 bytes of FP4
+// nibbles (2-bit) plus padding that makes the stride an odd multiple of 16, so
+// that the 16-byte reads of 16 consecutive pixels fall into distinct bank groups.
+constexpr int pix_stride(int cont) { return cont == 2 ? 48 : 80; }
 
 #ifdef DSQ_TRACE
 // Developer build only: per-wave phase timestamps (s_memtime ticks).
-__device__ unsigned long long dsq_trace_buf[4096 * 16];
+// Slots 0..15: phases of the kernel; 16..31: the taps of a wave's first stage.
+__device__ unsigned long long dsq_trace_buf[4096 * 32];
 #define DSQ_STAMP(slot)                                                              \
     do {                                                                             \
-        if (lane == 0 && grp == 0 && blk_y == 0 && blk_x < 1024 && (slot) < 16)      \
-            dsq_trace_buf[(blk_x * 4 + wave) * 16 + (slot)] = __builtin_amdgcn_s_memtime(); \
+        if (lane == 0 && blk_y == 0 && blk_x < 512 && (slot) < 32)                   \
+            dsq_trace_buf[(blk_x * 8 + grp * 4 + wave) * 32 + (slot)] = __builtin_amdgcn_s_memtime(); \
     } while (0)
 #else
 #define DSQ_STAMP(slot) do { } while (0)
@@ -101,10 +105,14 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
     constexpr int T = R * R;
     constexpr int UPP = CONT == 4 ? 2 : 1;        // 16-byte fetch units per patch pixel
     constexpr int KB_BYTES = 64 * CONT / 8;       // packed bytes of 64 channels
-    constexpr int WLANE = 4 * CONT;               // packed weight bytes per lane per (tile, cb, tap)
+    constexpr int WLANE = 16;                     // weight bytes per lane per (tile, cb, tap)
+    constexpr bool F4 = CONT == 2;                // 2-bit layers run on the FP4 matrix instruction
+    constexpr int KH = F4 ? 1 : 2;                // matrix instructions per 64 channels
+    constexpr int PIX_STRIDE = pix_stride(CONT);
     static_assert(WP * WC == 4, "four waves per workgroup");
     static_assert(64 * CT * WC <= 256, "one thread per staged channel constant");
-    typedef typename std::conditional<CONT == 4, v4i, v2i>::type wpack_t;
+    typedef v4i wpack_t;
+    typedef typename std::conditional<F4, v16f, v16i>::type macc_t;   // main-loop accumulator
 
     extern __shared__ __attribute__((aligned(16))) char lds[];
     // LDS: [patch buffer 0][patch buffer 1] (re-used by the epilogue as staging)
@@ -242,11 +250,9 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
                 *reinterpret_cast<v4i *>(d) = dsq_unpack16_c4((v2i){pk.x, pk.y});
                 *reinterpret_cast<v4i *>(d + 16) = dsq_unpack16_c4((v2i){pk.z, pk.w});
             } else {
-                // 16 packed bytes = 64 channels -> 64 int8
-                *reinterpret_cast<v4i *>(d) = dsq_unpack2((uint32_t)pk.x);
-                *reinterpret_cast<v4i *>(d + 16) = dsq_unpack2((uint32_t)pk.y);
-                *reinterpret_cast<v4i *>(d + 32) = dsq_unpack2((uint32_t)pk.z);
-                *reinterpret_cast<v4i *>(d + 48) = dsq_unpack2((uint32_t)pk.w);
+                // 16 packed bytes = 64 channels -> two K groups of 32 FP4 nibbles
+                *reinterpret_cast<v4i *>(d) = dsq_fp4_from_c2((uint32_t)pk.x, (uint32_t)pk.y);
+                *reinterpret_cast<v4i *>(d + 16) = dsq_fp4_from_c2((uint32_t)pk.z, (uint32_t)pk.w);
             }
         }
     };
@@ -294,22 +300,22 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
         frag_off[f] = prow * pl.RP + pcol * PIX_STRIDE + 16 * h;
     }
 
-    v16i acc[PF][CT];
-    const v16i zero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+    macc_t macc[PF][CT];
+    const macc_t zero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
     for (int f = 0; f < PF; ++f)
 #pragma unroll
-        for (int c = 0; c < CT; ++c) acc[f][c] = zero16;
+        for (int c = 0; c < CT; ++c) macc[f][c] = zero16;
 
     // One stage: all taps of 64 input channels.  HAS_NEXT: the weights and the
     // patch of stage next_cb are fetched / stored on the way.
     auto compute = [&](auto has_next, const char *buf, int cur_cb, int next_cb, char *nextbuf) {
         constexpr bool HAS_NEXT = decltype(has_next)::value;
-        v4i af[2][PF][2];
+        v4i af[2][PF][KH];
 #pragma unroll
         for (int f = 0; f < PF; ++f)
 #pragma unroll
-            for (int kh = 0; kh < 2; ++kh)
+            for (int kh = 0; kh < KH; ++kh)
                 af[0][f][kh] = *reinterpret_cast<const v4i *>(buf + frag_off[f] + 32 * kh);
 #pragma unroll
         for (int t = 0; t < T; ++t) {
@@ -318,35 +324,39 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
 #pragma unroll
                 for (int f = 0; f < PF; ++f)
 #pragma unroll
-                    for (int kh = 0; kh < 2; ++kh)
+                    for (int kh = 0; kh < KH; ++kh)
                         af[(t + 1) & 1][f][kh] =
                             *reinterpret_cast<const v4i *>(buf + frag_off[f] + tap_off + 32 * kh);
             }
-            v4i wf[CT][2];
+            v4i wf[CT][KH];
 #pragma unroll
             for (int c = 0; c < CT; ++c) {
                 const wpack_t wr = wreg[c][t % WD];
-                if (CONT == 4) {
-                    wf[c][0] = dsq_unpack16_c4((v2i){wr[0], wr[1]});
-                    wf[c][1] = dsq_unpack16_c4((v2i){wr[CONT == 4 ? 2 : 0], wr[CONT == 4 ? 3 : 1]});
+                if (F4) {
+                    wf[c][0] = wr;                       // FP4 nibbles go to the matrix cores as they are
                 } else {
-                    wf[c][0] = dsq_unpack2((uint32_t)wr[0]);
-                    wf[c][1] = dsq_unpack2((uint32_t)wr[1]);
+                    wf[c][0] = dsq_unpack16_c4((v2i){wr[0], wr[1]});
+                    wf[c][KH - 1] = dsq_unpack16_c4((v2i){wr[2], wr[3]});
                 }
                 if (t + WD < T) fetch_weight(c, t + WD, cur_cb);
                 else if (HAS_NEXT) fetch_weight(c, t + WD - T, next_cb);
             }
             // consecutive MFMAs go to different accumulators
 #pragma unroll
-            for (int kh = 0; kh < 2; ++kh)
+            for (int kh = 0; kh < KH; ++kh)
 #pragma unroll
                 for (int c = 0; c < CT; ++c)
 #pragma unroll
-                    for (int f = 0; f < PF; ++f)
-                        acc[f][c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[c][kh], af[t & 1][f][kh], acc[f][c], 0, 0, 0);
+                    for (int f = 0; f < PF; ++f) {
+                        if constexpr (F4)
+                            macc[f][c] = dsq_mfma_fp4(wf[c][kh], af[t & 1][f][kh], macc[f][c]);
+                        else
+                            macc[f][c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[c][kh], af[t & 1][f][kh], macc[f][c], 0, 0, 0);
+                    }
             // half way through the taps the next stage's patch has arrived:
             // unpack it into the other buffer while the matrix cores are busy
             if (HAS_NEXT && t == (T / 2)) store_patch(nextbuf);
+            if (cur_cb == grp) DSQ_STAMP(16 + t);
         }
     };
 
@@ -378,7 +388,7 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
         const int cb = grp + i * KS;
         fetch_patch(cb + KS);
         compute(std::true_type{}, patch_buf(i & 1), cb, cb + KS, patch_buf((i + 1) & 1));
-        if (i < 6) DSQ_STAMP(4 + i);
+        if (i < 1) DSQ_STAMP(4 + i);
         lds_barrier();
     }
     if (grp + n_full * KS < NCB) compute(std::false_type{}, patch_buf(n_full & 1), grp + n_full * KS, 0, nullptr);
@@ -386,6 +396,16 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
     if (KS > 1)
         for (int i = n_full; i < n_iter - 1; ++i) lds_barrier();
     DSQ_STAMP(14);
+
+    // the exact integer sums (the FP4 form accumulates them in quarter units)
+    v16i acc[PF][CT];
+#pragma unroll
+    for (int f = 0; f < PF; ++f)
+#pragma unroll
+        for (int c = 0; c < CT; ++c) {
+            if constexpr (F4) acc[f][c] = dsq_fp4_acc_to_int(macc[f][c]);
+            else acc[f][c] = macc[f][c];
+        }
 
     // ---- epilogue (see conv_epilogue.h for the algebra) ------------------------
     const int top = (1 << a.bits) - 1;
@@ -423,7 +443,9 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
     // channels (128 bytes) of 8 pixels instead of 16 bytes of 32 pixels.
     constexpr int ROWB = 128 + 16;                // staged bytes per pixel (+16: bank spread)
     constexpr int EPI_WAVE = 32 * ROWB + PF * 128;
+    DSQ_STAMP(5);
     lds_barrier();                              // every wave is done with the patch buffers
+    DSQ_STAMP(6);
     if (KS == 2) {
         // each group finishes the channel tiles c with c % 2 == grp: it hands the
         // partial sums of the other tiles to its partner wave through LDS and adds
@@ -443,7 +465,9 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
                     *reinterpret_cast<v4i *>(part + mine + ((f * (CT / 2) + c / 2) * 4 + q) * 1024) =
                         (v4i){acc[f][c][4 * q], acc[f][c][4 * q + 1], acc[f][c][4 * q + 2], acc[f][c][4 * q + 3]};
             }
+        DSQ_STAMP(7);
         lds_barrier();
+        DSQ_STAMP(8);
 #pragma unroll
         for (int f = 0; f < PF; ++f)
 #pragma unroll
@@ -457,6 +481,7 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
                 }
             }
     }
+    DSQ_STAMP(9);
     char *stage = lds + (grp * 4 + wave) * EPI_WAVE;
     int *m_stage = reinterpret_cast<int *>(stage + 32 * ROWB);
 
@@ -615,6 +640,7 @@ bool plan_patch(const DsqConvArgs &a, int BP, int BC, int PF, int CT, int UPT, i
         p.PR = PR;
         // row skew: consecutive tile pixels keep advancing by one pixel stride
         // (mod 256 bytes) when a fragment wraps from one strip row to the next
+        const int PIX_STRIDE = pix_stride(cont);
         int skew = ((TW * a.stride - p.PC) * PIX_STRIDE) % 256;
         if (skew < 0) skew += 256;
         p.RP = p.PC * PIX_STRIDE + (a.stride == 1 ? skew : 0);
@@ -696,7 +722,18 @@ int pick_tile(const DsqConvArgs &a)
     // yields enough workgroups and does not waste more than a quarter of its
     // channels; otherwise the 128x64 tile
     const int c_pad = ((a.C_out + 127) / 128) * 128;
-    if (a.C_out > 64 && 4 * (c_pad - a.C_out) <= c_pad && blocks(kMedium) >= 192) return TILE_MEDIUM;
+    if (a.C_out > 64 && 4 * (c_pad - a.C_out) <= c_pad && blocks(kMedium) >= 192) {
+        // 2-bit layers (FP4 path: the 256x128 tile fits its registers): take that
+        // tile when the 128x128 one leaves a nearly empty last round of workgroups
+        // (3 per CU, 768 at a time) and the large one (2 per CU, 512) does not
+        if (a.bits == 2 && !a.rq) {
+            const double bm = (double)blocks(kMedium), bl = (double)blocks(kLarge);
+            const double waste_m = (double)((blocks(kMedium) + 767) / 768 * 768) / bm;
+            const double waste_l = (double)((blocks(kLarge) + 511) / 512 * 512) / bl;
+            if (bl >= 256 && waste_m > 1.35 * waste_l) return TILE_LARGE;
+        }
+        return TILE_MEDIUM;
+    }
     if (blocks(kTall) >= 768) return TILE_TALL;
     return TILE_SMALL;
 }

@@ -1,6 +1,7 @@
 // dsq_conv2d, simple kernel: one wavefront per 32-pixel x 32-channel output
 // tile, operands fetched straight from global memory and unpacked in
-// registers.  It supports every geometry the library accepts and serves as the
+// registers (4-bit containers: int8 matrix instruction; 2-bit: the FP4 form, see
+// dsq_device.h).  It supports every geometry the library accepts and serves as the
 // fallback and as a cross-check for the tuned kernel.
 //
 // The GEMM view of Algorithm 1 step 5: rows = output channels, columns =
@@ -41,7 +42,30 @@ __global__ __launch_bounds__(256) void conv_simple_kernel(DsqConvArgs a)
     v16i acc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0;
-    for (int cb = 0; cb < NCB; ++cb) {
+    if (CONT == 2) {
+        // 2-bit layers: FP4 matrix instruction, 64 channels of one tap per step
+        v16f facc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) facc[r] = 0.f;
+        for (int cb = 0; cb < NCB; ++cb) {
+            for (int tap = 0; tap < T; ++tap) {
+                const int r = tap / a.R, s = tap % a.R;
+                const int iy = oy * a.stride - a.pad + r, ix = ox * a.stride - a.pad + s;
+                const bool inside = valid && iy >= 0 && iy < a.H && ix >= 0 && ix < a.W;
+                v4i af = {0, 0, 0, 0};
+                if (inside) {
+                    const char *p = act + (((size_t)n * a.H + iy) * a.W + ix) * row_bytes + cb * KB_BYTES + 8 * h;
+                    const v2i pk = *reinterpret_cast<const v2i *>(p);    // channels 32*h .. 32*h+31
+                    af = dsq_fp4_from_c2((uint32_t)pk.x, (uint32_t)pk.y);
+                }
+                const v4i wf = *reinterpret_cast<const v4i *>(
+                    wq + ((((size_t)ct * NCB + cb) * T + tap) * 64 + lane) * 4);
+                facc = dsq_mfma_fp4(wf, af, facc);
+            }
+        }
+        acc = dsq_fp4_acc_to_int(facc);
+    }
+    for (int cb = 0; cb < (CONT == 2 ? 0 : NCB); ++cb) {
         for (int tap = 0; tap < T; ++tap) {
             const int r = tap / a.R, s = tap % a.R;
             const int iy = oy * a.stride - a.pad + r, ix = ox * a.stride - a.pad + s;
@@ -53,12 +77,9 @@ __global__ __launch_bounds__(256) void conv_simple_kernel(DsqConvArgs a)
                 v4i af = {0, 0, 0, 0};
                 if (inside) {
                     const char *pk = p + (2 * kh + h) * KG_BYTES;   // channels 32*kh + 16*h ..
-                    if (CONT == 4) af = dsq_unpack16_c4(*reinterpret_cast<const v2i *>(pk));
-                    else af = dsq_unpack2(*reinterpret_cast<const uint32_t *>(pk));
+                    af = dsq_unpack16_c4(*reinterpret_cast<const v2i *>(pk));
                 }
-                v4i wf;
-                if (CONT == 4) wf = dsq_unpack16_c4(*reinterpret_cast<const v2i *>(wp + kh * WPL));
-                else wf = dsq_unpack2(wp[kh * WPL]);
+                const v4i wf = dsq_unpack16_c4(*reinterpret_cast<const v2i *>(wp + kh * WPL));
                 acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf, af, acc, 0, 0, 0);
             }
         }

@@ -6,6 +6,8 @@
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v2i __attribute__((ext_vector_type(2)));
 typedef int v16i __attribute__((ext_vector_type(16)));
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
 
 // Container width in bits for a given code width: 3-bit codes travel in
 // 4-bit containers.
@@ -77,4 +79,44 @@ __device__ __forceinline__ int dsq_bytesum(uint32_t w)
 {
     uint32_t s = (w & 0x00FF00FFu) + ((w >> 8) & 0x00FF00FFu);
     return (int)((s + (s >> 16)) & 0xFFFFu);
+}
+
+// ---- 2-bit layers on the FP4 matrix instruction ------------------------------
+//
+// A 2-bit code c in {0,1,2,3}, zero-extended to four bits, is the FP4 (e2m1)
+// encoding of c/2 (0, 0.5, 1.0, 1.5).  v_mfma_f32_32x32x64_f8f6f4 on such
+// operands therefore returns sum(ca*cw)/4 -- exactly: every product is a multiple
+// of 1/4 below 2.25 and the sums stay far below 2^24 quarter units -- at twice the
+// K per instruction of the int8 form and without any unpacking of the weights.
+// Lane L supplies row/column L%32 and the 32 K values of K group L/32 as 32
+// nibbles (16 bytes); results come back in the int8 instruction's layout.
+
+// 32 two-bit codes in the packed activation format (two words, channels 0..15 and
+// 16..31 of a K group) -> the lane's 128-bit FP4 operand.  Word d nibble n of the
+// result holds channel 16*(d/2) + 4*(d%2) + 8*(n%2) + n/2; dsq_pack_weights lays
+// 2-bit weights out in the same order.
+__device__ __forceinline__ v4i dsq_fp4_from_c2(uint32_t w0, uint32_t w1)
+{
+    v4i r;
+    r.x = (int)(w0 & 0x33333333u);
+    r.y = (int)((w0 >> 2) & 0x33333333u);
+    r.z = (int)(w1 & 0x33333333u);
+    r.w = (int)((w1 >> 2) & 0x33333333u);
+    return r;
+}
+
+// acc + (a . b) / 4 over the 64 K values the two 128-bit FP4 operands hold.
+__device__ __forceinline__ v16f dsq_mfma_fp4(v4i a, v4i b, v16f acc)
+{
+    const v8i a8 = {a.x, a.y, a.z, a.w, 0, 0, 0, 0}, b8 = {b.x, b.y, b.z, b.w, 0, 0, 0, 0};
+    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, acc, 4, 4, 0, 0, 0, 0);
+}
+
+// The integer sums behind a quarter-unit accumulator.
+__device__ __forceinline__ v16i dsq_fp4_acc_to_int(v16f acc)
+{
+    v16i r;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) r[i] = (int)(acc[i] * 4.0f);
+    return r;
 }

@@ -11,7 +11,13 @@ namespace {
 // (cb, tap, kh, h, dd) -> 8 (4-bit) or 16 (2-bit) consecutive input channels
 // starting at 64*cb + 32*kh + 16*h + 8*dd.  In memory the words of one
 // (32-channel tile, cb, tap) block are ordered [lane = 32*h + o%32][kh][dd], so
-// that a lane of the 32x32x32 MFMA finds its two K halves in 16 (8) adjacent bytes.
+// that a lane of the 32x32x32 MFMA finds its two K halves in 16 adjacent bytes.
+//
+// 2-bit layers (CONT == 2) feed the FP4 matrix instruction instead: one code per
+// 4-bit field, per lane the 32 channels 64*cb + 32*h + .. of its K group in 16
+// bytes, ordered [lane = 32*h + o%32][word d]; word d nibble n holds channel
+// offset 16*(d/2) + 4*(d%2) + 8*(n%2) + n/2 -- the order in which the kernels
+// spread packed 2-bit activation words into nibbles (dsq_fp4_from_c2).
 template <int CONT>
 __global__ __launch_bounds__(256) void pack_weights_kernel(
     const float *__restrict__ w, const float *__restrict__ l_w, const float *__restrict__ u_w,
@@ -38,7 +44,31 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(
         delta = ok ? dsq_delta(l, u, top) : __builtin_nanf("");
     }
     const int ct = o >> 5, row = o & 31;
-    const int nwords = NCB * T * 4 * WPL;
+    if (CONT == 2) {
+        const int nw = NCB * T * 8;
+        for (int i = tid; i < nw; i += 256) {
+            const int d = i & 3, h = (i >> 2) & 1;
+            const int tap = (i >> 3) % T, cb = (i >> 3) / T;
+            uint32_t word = 0;
+            int s = 0;
+            if (real) {
+#pragma unroll
+                for (int n = 0; n < 8; ++n) {
+                    const int c = 64 * cb + 32 * h + 16 * (d >> 1) + 4 * (d & 1) + 8 * (n & 1) + (n >> 1);
+                    int q = 0;
+                    if (c < C_in) {
+                        const size_t src = ((size_t)o * C_in + c) * T + tap;
+                        q = codes ? min((int)codes[src], top) : dsq_code(w[src], l, u, delta, top);
+                    }
+                    s += q;
+                    word |= (uint32_t)q << (4 * n);
+                }
+                if (s) atomicAdd(&stap[tap], s);
+            }
+            wq[((((size_t)ct * NCB + cb) * T + tap) * 64 + (32 * h + row)) * 4 + d] = word;
+        }
+    }
+    const int nwords = CONT == 2 ? 0 : NCB * T * 4 * WPL;
     for (int i = tid; i < nwords; i += 256) {
         int dd = i % WPL;
         int rest = i / WPL;

@@ -4,7 +4,8 @@
 
 For every layer of a config (shapes from :mod:`paper_1908_05033_amd.inputs`)
 it prints one JSON line: kernel time, effective int-TOPS (2*MACs/s, padding taps
-included), fraction of the int8 matrix peak, algorithmic bytes (packed codes in,
+included), fraction of the matrix peak of the instruction the layer runs on
+(int8: 5000 TOP/s; 2-bit layers use the FP4 form: 10100), algorithmic bytes (packed codes in,
 packed weights, pixel sums, fp32 out) and the GB/s they amount to.  Inputs are
 random tensors drawn on the GPU (timing does not depend on the values); launches
 are captured in a hipGraph that rotates over enough buffer sets to exceed the
@@ -22,7 +23,8 @@ import torch
 from . import binding as B
 from . import inputs
 
-INT8_PEAK_TOPS = 5000.0
+INT8_PEAK_TOPS = 5000.0      # dense int8 matrix peak (3- and 4-bit layers)
+FP4_PEAK_TOPS = 10100.0      # dense FP4 matrix peak (2-bit layers run on the FP4 instruction)
 HBM_PEAK_GBS = 8000.0
 
 
@@ -127,6 +129,8 @@ def bench_layer(L, kernel=0, min_bytes=600e6, max_sets=16, reps=5, chained=False
         "gemm_MxNxK": [L.N * L.Ho * L.Wo, L.C_out, L.C_in * L.R * L.S],
         "conv_us": round(tc * 1e6, 2), "conv_TOPS": round(tops, 1),
         "conv_frac_int8_peak": round(tops / INT8_PEAK_TOPS, 4),
+        "matrix_peak_TOPS": FP4_PEAK_TOPS if L.bits == 2 else INT8_PEAK_TOPS,
+        "conv_frac_matrix_peak": round(tops / (FP4_PEAK_TOPS if L.bits == 2 else INT8_PEAK_TOPS), 4),
         "conv_alg_MB": round(conv_bytes / 1e6, 2), "conv_GBps": round(conv_bytes / tc / 1e9, 1),
         "conv_frac_hbm_peak": round(conv_bytes / tc / 1e9 / HBM_PEAK_GBS, 4),
         "quant_us": round(tq * 1e6, 2), "quant_GBps": round(quant_bytes / tq / 1e9, 1),

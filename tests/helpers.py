@@ -41,7 +41,19 @@ def unpack_weights(packed_u8, C_out, C_in, R, bits):
     """Packed weight bytes -> codes [Cop, Cp, R, R] (OIHW order, padded)."""
     Cp, Cop = round_up(C_in, 64), round_up(C_out, 256)
     T = R * R
-    wpl = 2 if container(bits) == 4 else 1
+    if bits == 2:
+        # one code per 4-bit field; [ct][cb][tap][lane = 32h + row][word d], word d
+        # nibble n = channel 64cb + 32h + 16(d/2) + 4(d%2) + 8(n%2) + n/2
+        words = packed_u8.view(np.uint32).reshape(Cop // 32, Cp // 64, T, 2, 32, 4)
+        codes = np.empty((Cop // 32, 32, Cp // 64, 64, T), dtype=np.uint8)
+        for d in range(4):
+            for n in range(8):
+                nib = ((words[..., d] >> np.uint32(4 * n)) & np.uint32(15)).astype(np.uint8)   # [ct, cb, tap, h, row]
+                for h in range(2):
+                    ch = 32 * h + 16 * (d // 2) + 4 * (d % 2) + 8 * (n % 2) + n // 2
+                    codes[:, :, :, ch, :] = nib[:, :, :, h, :].transpose(0, 3, 1, 2)
+        return codes.reshape(Cop, Cp, R, R)
+    wpl = 2
     words = packed_u8.view(np.uint32).reshape(Cop // 32, Cp // 64, T, 64, 2, wpl)
     codes = unpack_words(words, bits)                 # [ct, cb, tap, lane, kh, 16]
     codes = codes.reshape(Cop // 32, Cp // 64, T, 2, 32, 2, 16)   # lane = 32*h + row
