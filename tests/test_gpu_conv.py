@@ -169,3 +169,22 @@ def test_config_4_mobilenetv2_pointwise_full_size_sampled(li):
 def test_config_5_vgg16_full_size_sampled(li):
     layer, inp = inputs.make_config_layer(5, li)
     _check_sampled(layer, inp, 0)
+
+
+@pytest.mark.parametrize("kernel", [0, 1, 3, 4, 6])
+@pytest.mark.parametrize("bits", [2, 4])
+def test_largest_codes_at_the_largest_k(bits, kernel):
+    """Every activation and weight code at its maximum over K = 9 * 512: the
+    largest accumulator the benchmark shapes can produce (41 472 at 2-bit on
+    the FP4 instruction's fp32 accumulators, 1 036 800 at 4-bit) must still be
+    the exact integer."""
+    top = (1 << bits) - 1
+    layer, inp = inputs.small_random_case(3, 1, 512, 6, 7, 64, 3, 1, 1, bits, l_a=0.0, u_a=2.0, asym_w=False)
+    inp["x"] = torch.full_like(inp["x"], 5.0)                       # clips to u_a: top code everywhere
+    w_codes = np.full((64, 512, 3, 3), top, dtype=np.uint8)
+    got = _run(layer, inp, kernel, w_codes=w_codes)
+    a_code, _ = oracle_layer(layer, inp, w_codes)
+    assert a_code.min() == top
+    acc = oracle.conv_codes(a_code, w_codes, 1, 1)
+    assert acc.max() == top * top * 9 * 512
+    assert np.array_equal(got["acc"], acc)
