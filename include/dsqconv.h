@@ -196,6 +196,36 @@ dsq_status dsq_conv2d_requant(const dsq_conv_desc *d, const void *act_packed,
                               void *codes_next, size_t codes_bytes,
                               int32_t *pix_code_sum_next, void *hip_stream);
 
+/* ---- training mode: the differentiable soft quantization function ---------
+ * Sec. 3.2: inside interval P_i = [l + i*Delta, l + (i+1)*Delta)
+ *     phi(x) = s * tanh(k * (x - m_i)),  m_i = l + (i + 0.5)*Delta
+ *     Q_S(x) = l + Delta * (i + (phi(x) + 1)/2);   Q_S = l for x < l, u for x > u
+ * Sec. 3.3: k = log(2/alpha - 1)/Delta and s = 1/(1 - alpha); Sec. 4.3 keeps
+ * alpha in (0, 0.5) (otherwise DSQ_ERR_RANGE) and k <= 1000 (when the cap is
+ * active, s = 1/tanh(0.5*k*Delta) so that the intervals still join).
+ * Elementwise binary32 arithmetic on constants the host derives in binary64;
+ * NaN inputs give NaN.  n <= 2^31 - 1 elements of any shape, contiguous.
+ *
+ * dsq_soft_quantize_fwd   y[j] = Q_S(x[j])
+ * dsq_soft_quantize_bwd   Algorithm 1, back-propagation, for one tensor:
+ *     grad_x[j]         = grad_y[j] * dQ_S/dx
+ *     grad_alpha_l_u[0] = sum_j grad_y[j] * dQ_S/dalpha     (Sec. 3.3)
+ *     grad_alpha_l_u[1] = sum_j grad_y[j] * dQ_S/dl         (Sec. 3.4)
+ *     grad_alpha_l_u[2] = sum_j grad_y[j] * dQ_S/du         (Sec. 3.4)
+ *   with the interval index held fixed; outside [l, u] only the clipped bound
+ *   receives gradient.  grad_alpha_l_u is device memory, 3 doubles, 16-byte
+ *   aligned, overwritten (cleared by a fill kernel on the stream, then
+ *   accumulated in binary64, so the order of the partial sums moves the result
+ *   by about 1e-16 relative).
+ */
+dsq_status dsq_soft_quantize_fwd(const float *x, size_t n, float l, float u,
+                                 float alpha, int bits, float *y,
+                                 void *hip_stream);
+dsq_status dsq_soft_quantize_bwd(const float *x, const float *grad_y, size_t n,
+                                 float l, float u, float alpha, int bits,
+                                 float *grad_x, double *grad_alpha_l_u,
+                                 void *hip_stream);
+
 /* Selects the convolution kernel: 0 = automatic (default), 1 = the simple
  * one-wave-per-tile kernel, 2 = the LDS-patch kernel with its tile chosen by
  * problem size, 3 / 4 / 5 / 6 = the LDS-patch kernel with the 128x64 / 128x128 /

@@ -59,6 +59,13 @@ def forward(x, l, u, alpha, bits):
 def partials(x, l, u, alpha, bits):
     """(dy/dx, dy/dalpha, dy/dl, dy/du), each float64 with the shape of x."""
     x = np.asarray(x, dtype=np.float64)
+    # (infinite inputs produce invalid intermediates in the branch that the final
+    # selection discards)
+    with np.errstate(invalid="ignore", over="ignore"):
+        return _partials(x, l, u, alpha, bits)
+
+
+def _partials(x, l, u, alpha, bits):
     levels = float((1 << bits) - 1)
     delta, k, s, capped = shape_parameters(l, u, alpha, bits)
     i = interval_index(x, l, u, bits)

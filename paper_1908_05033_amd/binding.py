@@ -21,6 +21,7 @@ DSQ_OK = 0
 EXPORTS = [
     "dsq_act_packed_bytes", "dsq_wgt_packed_bytes", "dsq_wgt_aux_bytes",
     "dsq_quantize_act", "dsq_pack_weights", "dsq_conv2d", "dsq_conv2d_requant",
+    "dsq_soft_quantize_fwd", "dsq_soft_quantize_bwd",
     "dsq_set_conv_kernel", "dsq_status_string",
 ]
 
@@ -66,6 +67,10 @@ def load_library():
     lib.dsq_conv2d_requant.restype = i
     lib.dsq_conv2d_requant.argtypes = [C.POINTER(dsq_conv_desc), vp, vp, f, f, vp, vp, vp, vp, i, f, f, i,
                                        vp, sz, vp, vp]
+    lib.dsq_soft_quantize_fwd.restype = i
+    lib.dsq_soft_quantize_fwd.argtypes = [vp, sz, f, f, f, i, vp, vp]
+    lib.dsq_soft_quantize_bwd.restype = i
+    lib.dsq_soft_quantize_bwd.argtypes = [vp, vp, sz, f, f, f, i, vp, vp, vp]
     lib.dsq_set_conv_kernel.restype = i
     lib.dsq_set_conv_kernel.argtypes = [i]
     lib.dsq_status_string.restype = C.c_char_p
@@ -153,6 +158,17 @@ def dsq_conv2d_requant(desc, act_packed, pix_code_sum, l_a, u_a, w_packed, w_aux
         l_next, u_next, bits_next,
         _dev_ptr(codes_next, torch.uint8), codes_next.numel() if codes_next is not None else 0,
         _dev_ptr(pix_code_sum_next, torch.int32), _stream(stream)))
+
+
+def dsq_soft_quantize_fwd(x, l, u, alpha, bits, y, stream=None):
+    _check(load_library().dsq_soft_quantize_fwd(_dev_ptr(x, torch.float32), x.numel(), l, u, alpha, bits,
+                                                _dev_ptr(y, torch.float32), _stream(stream)))
+
+
+def dsq_soft_quantize_bwd(x, grad_y, l, u, alpha, bits, grad_x, grad_alpha_l_u, stream=None):
+    _check(load_library().dsq_soft_quantize_bwd(
+        _dev_ptr(x, torch.float32), _dev_ptr(grad_y, torch.float32), x.numel(), l, u, alpha, bits,
+        _dev_ptr(grad_x, torch.float32), _dev_ptr(grad_alpha_l_u, torch.float64), _stream(stream)))
 
 
 def dsq_set_conv_kernel(which):

@@ -171,6 +171,75 @@ dsq_status dsq_conv2d_requant(const dsq_conv_desc *d, const void *act_packed,
     return launch_conv(a, (hipStream_t)hip_stream);
 }
 
+namespace {
+
+// Shape of the DSQ function from (l, u, alpha, bits): Sec. 3.3 of the paper,
+// with the cap k <= 1000 of Sec. 4.3; when the cap is active s comes from its
+// definition 1/tanh(0.5*k*Delta) so that neighbouring intervals still join.
+dsq_status soft_args(float l, float u, float alpha, int bits, DsqSoftArgs &p)
+{
+    if (!bits_ok(bits)) return DSQ_ERR_BITS;
+    if (!range_ok(l, u)) return DSQ_ERR_RANGE;
+    if (!(alpha > 0.0f && alpha < 0.5f)) return DSQ_ERR_RANGE;
+    const double levels = (double)((1 << bits) - 1);
+    const double delta = ((double)u - (double)l) / levels;
+    if (!(delta > 0.0)) return DSQ_ERR_RANGE;
+    const double a = (double)alpha;
+    const double c = log(2.0 / a - 1.0);
+    double k = c / delta, s, k_a, k_l, k_u, s_a, s_l, s_u;
+    if (k > 1000.0) {
+        k = 1000.0;
+        const double T = tanh(0.5 * k * delta);
+        s = 1.0 / T;
+        k_a = k_l = k_u = 0.0;
+        s_a = 0.0;
+        s_l = (1.0 - T * T) * k / (2.0 * levels * T * T);
+        s_u = -s_l;
+    } else {
+        s = 1.0 / (1.0 - a);
+        k_a = -2.0 / (a * (2.0 - a)) / delta;
+        k_l = c / (levels * delta * delta);
+        k_u = -k_l;
+        s_a = 1.0 / ((1.0 - a) * (1.0 - a));
+        s_l = s_u = 0.0;
+    }
+    p.l = l; p.u = u; p.delta = (float)delta; p.inv_delta = (float)(1.0 / delta);
+    p.last_interval = (float)(levels - 1.0); p.inv_levels = (float)(1.0 / levels);
+    p.k = (float)k; p.s = (float)s;
+    p.k_a = (float)k_a; p.k_l = (float)k_l; p.k_u = (float)k_u;
+    p.s_a = (float)s_a; p.s_l = (float)s_l; p.s_u = (float)s_u;
+    return DSQ_OK;
+}
+
+}  // namespace
+
+dsq_status dsq_soft_quantize_fwd(const float *x, size_t n, float l, float u, float alpha, int bits,
+                                 float *y, void *hip_stream)
+{
+    if (!x || !y) return DSQ_ERR_NULL;
+    if (n == 0 || n > (size_t)kMaxElems) return DSQ_ERR_SHAPE;
+    if (!aligned16(x) || !aligned16(y)) return DSQ_ERR_ALIGN;
+    DsqSoftArgs p;
+    const dsq_status st = soft_args(l, u, alpha, bits, p);
+    if (st != DSQ_OK) return st;
+    return dsq_launch_soft_fwd(x, y, n, p, (hipStream_t)hip_stream) == hipSuccess ? DSQ_OK : DSQ_ERR_HIP;
+}
+
+dsq_status dsq_soft_quantize_bwd(const float *x, const float *grad_y, size_t n, float l, float u,
+                                 float alpha, int bits, float *grad_x, double *grad_alpha_l_u,
+                                 void *hip_stream)
+{
+    if (!x || !grad_y || !grad_x || !grad_alpha_l_u) return DSQ_ERR_NULL;
+    if (n == 0 || n > (size_t)kMaxElems) return DSQ_ERR_SHAPE;
+    if (!aligned16(x) || !aligned16(grad_y) || !aligned16(grad_x) || !aligned16(grad_alpha_l_u))
+        return DSQ_ERR_ALIGN;
+    DsqSoftArgs p;
+    const dsq_status st = soft_args(l, u, alpha, bits, p);
+    if (st != DSQ_OK) return st;
+    return dsq_launch_soft_bwd(x, grad_y, grad_x, n, p, grad_alpha_l_u, (hipStream_t)hip_stream) == hipSuccess
+               ? DSQ_OK : DSQ_ERR_HIP;
+}
+
 int dsq_set_conv_kernel(int which)
 {
     int prev = g_conv_kernel;

@@ -43,6 +43,21 @@ hipError_t dsq_launch_pack_weights(const float *w, const float *l_w, const float
                                    const uint8_t *codes, int C_out, int C_in, int R, int bits,
                                    void *w_packed, void *w_aux, hipStream_t stream);
 
+// Constants of the training-mode DSQ function for one tensor, computed on the
+// host in binary64 and rounded once.
+struct DsqSoftArgs {
+    float l, u, delta, inv_delta;
+    float last_interval;      // 2^b - 2
+    float inv_levels;         // 1 / (2^b - 1)
+    float k, s;
+    float k_a, k_l, k_u;      // how k moves with alpha, l, u (0 when k is capped)
+    float s_a, s_l, s_u;      // how s moves with alpha, l, u
+};
+
+hipError_t dsq_launch_soft_fwd(const float *x, float *y, size_t n, const DsqSoftArgs &p, hipStream_t stream);
+hipError_t dsq_launch_soft_bwd(const float *x, const float *gy, float *gx, size_t n, const DsqSoftArgs &p,
+                               double *sums, hipStream_t stream);
+
 // Sets n int32 words to zero with a kernel (safe inside graph capture).
 hipError_t dsq_launch_fill_zero(int32_t *p, size_t n, hipStream_t stream);
 

@@ -233,3 +233,14 @@ def affine_params(seed, C_out, shift_std=0.3):
     scale = torch.where(flip, -scale, scale)
     shift = torch.randn(C_out, generator=g, dtype=torch.float32) * shift_std
     return scale.numpy().astype(np.float32), shift.numpy().astype(np.float32)
+
+
+def soft_quant_case(seed, n, l, u):
+    """Inputs of the training-mode kernels: a tensor that covers [l, u] with both
+    tails (about a tenth of the values clipped on each side) and an upstream
+    gradient ~ N(0, 1).  float32 CPU tensors."""
+    g = torch.Generator().manual_seed(BASE_SEED + 500 + seed)
+    mid, half = 0.5 * (l + u), 0.5 * (u - l)
+    x = torch.randn(n, generator=g, dtype=torch.float32) * (0.78 * half) + mid
+    grad_y = torch.randn(n, generator=g, dtype=torch.float32)
+    return x, grad_y
