@@ -240,10 +240,10 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
 #pragma unroll
         for (int k = 0; k < UPT; ++k) pre[k] = *reinterpret_cast<const v4i *>(base + src_off[k]);
     };
-    auto store_patch = [&](char *buf) {
+    auto store_units = [&](char *buf, const v4i (&units)[UPT]) {
 #pragma unroll
         for (int k = 0; k < UPT; ++k) {
-            const v4i pk = (src_valid >> k & 1) ? pre[k] : (v4i){0, 0, 0, 0};
+            const v4i pk = (src_valid >> k & 1) ? units[k] : (v4i){0, 0, 0, 0};
             char *d = buf + dst_off[k];
             if (CONT == 4) {
                 // 16 packed bytes = 32 channels -> 32 int8
@@ -256,6 +256,7 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
             }
         }
     };
+    auto store_patch = [&](char *buf) { store_units(buf, pre); };
     fetch_patch(cb_first);
     DSQ_STAMP(13);
     // side tables, needed only after the main loop: the pixels' code sums and the
@@ -391,6 +392,41 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
         if (i < 1) DSQ_STAMP(4 + i);
         lds_barrier();
     }
+    // ---- side values of the epilogue (see conv_epilogue.h for the algebra) ------
+    const int top = (1 << a.bits) - 1;
+    const float delta_a = dsq_delta(a.l_a, a.u_a, top);
+    // fast path: NHWC fp32 output only, l_a = 0, C_out a multiple of 4
+    const bool fast = !a.out_nchw && (a.C_out & 3) == 0 && a.l_a == 0.0f && a.acc == nullptr;
+    // per fragment: SA = code sums of the patch pixels under the taps (0 in the padding)
+    double dsa[PF];
+    auto sum_sa = [&]() {
+#pragma unroll
+        for (int f = 0; f < PF; ++f) {
+            int sa = 0;
+#pragma unroll
+            for (int t = 0; t < T; ++t) sa += pix_lds[frag_pp[f] + (t / R) * pl.PC + (t % R)];
+            dsa[f] = (double)sa;
+        }
+    };
+    // Da*Dw and Da*l_w of this lane's channels of one tile: 4 groups of 4
+    auto load_pq = [&](int c, double (&P)[16], double (&Q)[16]) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int ol = (wc * CT + c) * 32 + 8 * q + 4 * h;   // channel inside the workgroup
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { P[4 * q + j] = pq_lds[ol + j]; Q[4 * q + j] = pq_lds[BC + ol + j]; }
+        }
+    };
+    // With two wave groups (two waves per SIMD, registers to spare) a wave finishes a
+    // single tile; its constants and code sums are fetched before the last stage so
+    // that these LDS reads run under the matrix instructions instead of after them.
+    // (The tables were written before the first barrier.)
+    double P0[16], Q0[16];
+    const bool early_tables = KS == 2 && CT == 2;
+    if (early_tables) {
+        sum_sa();
+        if (fast) load_pq(grp, P0, Q0);
+    }
     if (grp + n_full * KS < NCB) compute(std::false_type{}, patch_buf(n_full & 1), grp + n_full * KS, 0, nullptr);
     // every wave of the workgroup takes part in n_iter - 1 stage barriers
     if (KS > 1)
@@ -407,35 +443,8 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
             else acc[f][c] = macc[f][c];
         }
 
-    // ---- epilogue (see conv_epilogue.h for the algebra) ------------------------
-    const int top = (1 << a.bits) - 1;
-    const float delta_a = dsq_delta(a.l_a, a.u_a, top);
-    // fast path: NHWC fp32 output only, l_a = 0, C_out a multiple of 4
-    const bool fast = !a.out_nchw && (a.C_out & 3) == 0 && a.l_a == 0.0f && a.acc == nullptr;
-
-    // per fragment: SA = code sums of the patch pixels under the taps (0 in the padding)
-    double dsa[PF];
-#pragma unroll
-    for (int f = 0; f < PF; ++f) {
-        int sa = 0;
-#pragma unroll
-        for (int t = 0; t < T; ++t) sa += pix_lds[frag_pp[f] + (t / R) * pl.PC + (t % R)];
-        dsa[f] = (double)sa;
-    }
-
-    // Da*Dw and Da*l_w of this lane's channels of one tile: 4 groups of 4
-    auto load_pq = [&](int c, double (&P)[16], double (&Q)[16]) {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int ol = (wc * CT + c) * 32 + 8 * q + 4 * h;   // channel inside the workgroup
-#pragma unroll
-            for (int j = 0; j < 4; ++j) { P[4 * q + j] = pq_lds[ol + j]; Q[4 * q + j] = pq_lds[BC + ol + j]; }
-        }
-    };
-    // with two wave groups a wave finishes a single tile: fetch its constants now,
-    // ahead of the exchange of partial sums
-    double P0[16], Q0[16];
-    if (KS == 2 && CT == 2 && fast) load_pq(grp, P0, Q0);
+    // ---- epilogue --------------------------------------------------------------
+    if (!early_tables) sum_sa();
 
     // The results of a 32x32 tile sit in the lanes as [pixel = lane%32][4 groups
     // of 4 channels].  They are staged through this wave's slice of the (now idle)
