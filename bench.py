@@ -38,7 +38,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=200)
-    ap.add_argument("--config", type=int, default=2, help="BASELINE config (1 or 2)")
+    ap.add_argument("--config", type=int, default=2, help="benchmark config (1 or 2)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--serial", action="store_true", help="no overlap between steps of different batches")
     ap.add_argument("--sets", type=int, default=0, help="buffer sets to rotate over (0 = auto)")
@@ -52,7 +52,7 @@ def main():
     args = parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (the path shards over the batch "
-              "with no exchange; see DESIGN.md); run with --gpus 1", file=sys.stderr)
+              "with no exchange step); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np

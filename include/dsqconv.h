@@ -1,5 +1,5 @@
 /*
- * dsqconv.h -- C ABI of libdsqconv: b-bit (2..4) uniformly quantized conv2d
+ * dsqconv.h -- C ABI of libdsqconv: b-bit (1..4) uniformly quantized conv2d
  * executed as integer arithmetic on codes, for AMD MI355X (gfx950).
  *
  * The three calls are the deployment form of one DSQ-quantized convolution
@@ -24,7 +24,10 @@
  *   - Arguments are validated on the host before anything is launched; on any
  *     error nothing has been enqueued.  Errors are return codes only.
  *   - Device pointers must be 16-byte aligned.
- *   - bits is 2, 3 or 4, the same for activations and weights of one layer.
+ *   - bits is 1, 2, 3 or 4, the same for activations and weights of one layer.
+ *     bits = 1 is the binary case of Sec. 3.1: with (l, u) = (-1, +1) the two
+ *     levels are sgn(x) (code 1 for x >= 0), and any other (l, u) gives the
+ *     two-level quantizer with levels l and u.
  *
  * Quantizer (Sec. 3.1 uniform quantizer with range [l,u]; tie rule from
  * sgn(0)=+1 applied at the interval midpoints m_i of Sec. 3.2), evaluated in
@@ -35,7 +38,7 @@
  *     code  = clamp((int)floor(t + 0.5), 0, 2^b - 1)
  * The level a code stands for is l + Delta*code (Alg. 1 step 4).
  *
- * Packed code format ("container" = 4 bits for b in {3,4}, 2 bits for b=2)
+ * Packed code format ("container" = 4 bits for b in {3,4}, 2 bits for b in {1,2})
  *   A 32-bit word holds 8 (4-bit) or 16 (2-bit) consecutive channels
  *   c0, c1, ...; byte j (j=0..3) of the word is
  *       4-bit:  c[j] | c[j+4] << 4
@@ -52,7 +55,7 @@
  *       channels 64*cb + 32*kh + 16*h + 0..15 of output channel o as two words of
  *       the format above -- the operand order of the 32x32x32 int8 matrix
  *       instruction;
- *     bits 2: the lane's 16 bytes are the 32 channels 64*cb + 32*h + 0..31, word d
+ *     bits 1, 2: the lane's 16 bytes are the 32 channels 64*cb + 32*h + 0..31, word d
  *       (0..3) nibble n (0..7, from the low end) holding channel offset
  *       16*(d/2) + 4*(d%2) + 8*(n%2) + n/2.  A 2-bit code zero-extended to four
  *       bits is the FP4 (e2m1) encoding of code/2, so these words are operands
@@ -73,7 +76,7 @@ extern "C" {
 typedef enum {
     DSQ_OK = 0,
     DSQ_ERR_NULL = 1,        /* a required pointer is NULL */
-    DSQ_ERR_BITS = 2,        /* bits not in {2,3,4} */
+    DSQ_ERR_BITS = 2,        /* bits not in {1,2,3,4} */
     DSQ_ERR_RANGE = 3,       /* !(l < u) or a bound is not finite */
     DSQ_ERR_SHAPE = 4,       /* a dimension <= 0, or Ho/Wo <= 0 */
     DSQ_ERR_UNSUPPORTED = 5, /* R != S, R not in {1,3}, stride not in {1,2},

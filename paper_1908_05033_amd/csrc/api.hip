@@ -10,7 +10,7 @@ namespace {
 
 int g_conv_kernel = 0;   // 0 auto, 1 simple, 2 patch (auto tile), 3..6 patch with a fixed tile
 
-bool bits_ok(int bits) { return bits >= 2 && bits <= 4; }
+bool bits_ok(int bits) { return bits >= 1 && bits <= 4; }
 bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
 bool range_ok(float l, float u) { return isfinite(l) && isfinite(u) && l < u; }
 const long long kMaxElems = (1LL << 31) - 1;
@@ -252,7 +252,7 @@ const char *dsq_status_string(dsq_status s)
     switch (s) {
     case DSQ_OK: return "ok";
     case DSQ_ERR_NULL: return "a required pointer is NULL";
-    case DSQ_ERR_BITS: return "bits must be 2, 3 or 4";
+    case DSQ_ERR_BITS: return "bits must be 1, 2, 3 or 4";
     case DSQ_ERR_RANGE: return "clip range must be finite with l < u";
     case DSQ_ERR_SHAPE: return "invalid tensor or filter shape";
     case DSQ_ERR_UNSUPPORTED: return "unsupported geometry, layout or tensor size";

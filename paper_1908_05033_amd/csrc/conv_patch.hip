@@ -735,7 +735,7 @@ int pick_tile(const DsqConvArgs &a)
         // 2-bit layers (FP4 path: the 256x128 tile fits its registers): take that
         // tile when the 128x128 one leaves a nearly empty last round of workgroups
         // (3 per CU, 768 at a time) and the large one (2 per CU, 512) does not
-        if (a.bits == 2 && !a.rq) {
+        if (dsq_container(a.bits) == 2 && !a.rq) {
             const double bm = (double)blocks(kMedium), bl = (double)blocks(kLarge);
             const double waste_m = (double)((blocks(kMedium) + 767) / 768 * 768) / bm;
             const double waste_l = (double)((blocks(kLarge) + 511) / 512 * 512) / bl;

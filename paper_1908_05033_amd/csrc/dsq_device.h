@@ -10,8 +10,8 @@ typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 
 // Container width in bits for a given code width: 3-bit codes travel in
-// 4-bit containers.
-__host__ __device__ constexpr int dsq_container(int bits) { return bits == 2 ? 2 : 4; }
+// 4-bit containers, 1-bit codes (the binary case) in 2-bit containers.
+__host__ __device__ constexpr int dsq_container(int bits) { return bits <= 2 ? 2 : 4; }
 __host__ __device__ constexpr int dsq_round_up(int x, int m) { return (x + m - 1) / m * m; }
 
 // Uniform quantizer of the paper's Sec. 3.1 with clip range [l,u]; a value at

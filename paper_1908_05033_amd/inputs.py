@@ -7,8 +7,8 @@ which is why both the GPU tests and the CPU oracle tests may use it.
 The tensors stand in for the ImageNet activations and trained weights the
 paper ran on (Sec. 4.1, 4.5): only layer shapes and value distributions are
 taken -- ResNet-18 and MobileNetV2 from the paper's network list (Sec. 4.1),
-with the first convolution left in floating point as the paper does
-("all layers except the first and the last are quantized").
+with the first convolution (and the final classifier) left in floating
+point, as in the paper's experimental setup.
 
 Everything is generated on the CPU with a counter-seeded torch generator, in
 NCHW / OIHW float32, so that a CPU checker and the GPU see identical bits.

@@ -110,7 +110,7 @@ def bench_layer(L, kernel=0, min_bytes=600e6, max_sets=16, reps=5, chained=False
     finally:
         B.dsq_set_conv_kernel(prev)
     # algorithmic conv bytes: packed weights are counted at the packed code width
-    cont = 2 if L.bits == 2 else 4
+    cont = 2 if L.bits <= 2 else 4
     w_alg = L.C_out * L.C_in * L.R * L.S * cont // 8
     conv_bytes = code_bytes + pix_bytes + w_alg + out_bytes
     quant_bytes = in_bytes + code_bytes + pix_bytes
@@ -129,8 +129,8 @@ def bench_layer(L, kernel=0, min_bytes=600e6, max_sets=16, reps=5, chained=False
         "gemm_MxNxK": [L.N * L.Ho * L.Wo, L.C_out, L.C_in * L.R * L.S],
         "conv_us": round(tc * 1e6, 2), "conv_TOPS": round(tops, 1),
         "conv_frac_int8_peak": round(tops / INT8_PEAK_TOPS, 4),
-        "matrix_peak_TOPS": FP4_PEAK_TOPS if L.bits == 2 else INT8_PEAK_TOPS,
-        "conv_frac_matrix_peak": round(tops / (FP4_PEAK_TOPS if L.bits == 2 else INT8_PEAK_TOPS), 4),
+        "matrix_peak_TOPS": FP4_PEAK_TOPS if L.bits <= 2 else INT8_PEAK_TOPS,
+        "conv_frac_matrix_peak": round(tops / (FP4_PEAK_TOPS if L.bits <= 2 else INT8_PEAK_TOPS), 4),
         "conv_alg_MB": round(conv_bytes / 1e6, 2), "conv_GBps": round(conv_bytes / tc / 1e9, 1),
         "conv_frac_hbm_peak": round(conv_bytes / tc / 1e9 / HBM_PEAK_GBS, 4),
         "quant_us": round(tq * 1e6, 2), "quant_GBps": round(quant_bytes / tq / 1e9, 1),

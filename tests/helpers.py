@@ -9,7 +9,7 @@ from paper_1908_05033_amd import binding as B
 
 
 def container(bits):
-    return 2 if bits == 2 else 4
+    return 2 if bits <= 2 else 4
 
 
 def round_up(x, m):
@@ -41,7 +41,7 @@ def unpack_weights(packed_u8, C_out, C_in, R, bits):
     """Packed weight bytes -> codes [Cop, Cp, R, R] (OIHW order, padded)."""
     Cp, Cop = round_up(C_in, 64), round_up(C_out, 256)
     T = R * R
-    if bits == 2:
+    if bits <= 2:
         # one code per 4-bit field; [ct][cb][tap][lane = 32h + row][word d], word d
         # nibble n = channel 64cb + 32h + 16(d/2) + 4(d%2) + 8(n%2) + n/2
         words = packed_u8.view(np.uint32).reshape(Cop // 32, Cp // 64, T, 2, 32, 4)

@@ -61,7 +61,7 @@ def test_quantize_act_rejects_bad_arguments():
     assert _q(x=None) == 1
     assert _q(codes=None) == 1
     assert _q(pix=None) == 1
-    assert _q(bits=1) == 2 and _q(bits=5) == 2
+    assert _q(bits=0) == 2 and _q(bits=5) == 2
     assert _q(l=1.0, u=1.0) == 3 and _q(l=2.0, u=1.0) == 3
     assert _q(l=float("nan")) == 3 and _q(u=float("inf")) == 3
     assert _q(N=0) == 4 and _q(Cc=-1) == 4

@@ -70,7 +70,7 @@ SMALL = [  # N, C_in, H, W, C_out, R, stride, pad
 
 
 @pytest.mark.parametrize("kernel", KERNELS)
-@pytest.mark.parametrize("bits", [2, 3, 4])
+@pytest.mark.parametrize("bits", [1, 2, 3, 4])
 @pytest.mark.parametrize("geom", SMALL)
 def test_small_geometries_generic_bounds(geom, bits, kernel):
     """Ragged sizes, l_a != 0 (so the padding-dependent terms matter) and
@@ -188,3 +188,20 @@ def test_largest_codes_at_the_largest_k(bits, kernel):
     acc = oracle.conv_codes(a_code, w_codes, 1, 1)
     assert acc.max() == top * top * 9 * 512
     assert np.array_equal(got["acc"], acc)
+
+
+@pytest.mark.parametrize("kernel", [0, 1, 3, 4, 6])
+def test_binary_layer_is_the_convolution_of_signs(kernel):
+    """bits = 1 with (l, u) = (-1, +1) is the binary quantizer of Sec. 3.1
+    (sgn, with sgn(0) = +1): the layer output must be exactly the zero-padded
+    cross-correlation of sgn(a) and sgn(w), an integer-valued tensor."""
+    import torch.nn.functional as F
+    layer, inp = inputs.small_random_case(9, 2, 192, 9, 8, 80, 3, 1, 1, 1, l_a=-1.0, u_a=1.0)
+    inp["x"] = inp["x"] - inp["x"].mean()
+    inp["x"][0, :, 0, 0] = 0.0                          # sgn(0) = +1
+    inp["l_w"] = -np.ones(80, np.float32)
+    inp["u_w"] = np.ones(80, np.float32)
+    got = _run(layer, inp, kernel)
+    sgn = lambda t: torch.where(t >= 0, 1.0, -1.0).double()
+    want = F.conv2d(sgn(inp["x"]), sgn(inp["w"]), padding=1).numpy()
+    assert np.array_equal(got["out"].astype(np.float64), want)

@@ -32,7 +32,7 @@ def _check_act(x, l, u, bits, layout):
 
 
 @pytest.mark.parametrize("layout", [B.DSQ_NHWC, B.DSQ_NCHW])
-@pytest.mark.parametrize("bits", [2, 3, 4])
+@pytest.mark.parametrize("bits", [1, 2, 3, 4])
 @pytest.mark.parametrize("shape", [(2, 64, 5, 7), (1, 24, 9, 11), (3, 3, 4, 5), (1, 144, 6, 6),
                                    (2, 256, 7, 7), (1, 320, 3, 5), (1, 576, 4, 3), (1, 1280, 2, 3),
                                    (2, 130, 3, 3)])
@@ -43,7 +43,7 @@ def test_codes_and_pixel_sums_small(shape, bits, layout):
 
 
 @pytest.mark.parametrize("layout", [B.DSQ_NHWC, B.DSQ_NCHW])
-@pytest.mark.parametrize("bits", [2, 3, 4])
+@pytest.mark.parametrize("bits", [1, 2, 3, 4])
 def test_ties_specials_and_float_neighbours_of_every_threshold(bits, layout):
     """Exact midpoints (Delta a power of two), +-inf, NaN, +-0, and for a
     generic range every float within a few ulps of each rounding threshold."""
@@ -76,7 +76,7 @@ def test_codes_at_config_sizes(cfg):
 
 def test_codes_large_r18_layer_all_bits():
     layer, inp = inputs.make_config_layer(3, 0, bits=4, batch=8)
-    for bits in (2, 3, 4):
+    for bits in (1, 2, 3, 4):
         _check_act(inp["x"], inp["l_a"], inp["u_a"], bits, B.DSQ_NHWC)
 
 
@@ -92,7 +92,7 @@ def _pack_gpu(w, lw, uw, bits, codes=None):
     return unpack_weights(wp.cpu().numpy(), Co, Ci, R, bits), split_aux(aux.cpu().numpy(), Co, R)
 
 
-@pytest.mark.parametrize("bits", [2, 3, 4])
+@pytest.mark.parametrize("bits", [1, 2, 3, 4])
 @pytest.mark.parametrize("shape", [(64, 64, 3, 3), (24, 144, 1, 1), (144, 24, 1, 1), (5, 3, 3, 3),
                                    (300, 70, 3, 3)])
 def test_weight_codes_layout_and_side_tables(shape, bits):

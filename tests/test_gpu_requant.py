@@ -101,7 +101,7 @@ SMALL = [  # N, C_in, H, W, C_out, R, stride, pad
 
 @pytest.mark.parametrize("kernel", KERNELS)
 @pytest.mark.parametrize("l_a,relu", [(0.0, True), (-0.4, False)])
-@pytest.mark.parametrize("bits,bits_n", [(4, 4), (2, 2), (3, 4), (4, 2)])
+@pytest.mark.parametrize("bits,bits_n", [(4, 4), (2, 2), (3, 4), (4, 2), (1, 1)])
 @pytest.mark.parametrize("geom", SMALL)
 def test_small_geometries(geom, bits, bits_n, l_a, relu, kernel):
     """l_a = 0 takes the tuned kernel's own chained epilogue; l_a != 0 (terms that
