@@ -1,6 +1,7 @@
 // C ABI of libdsqconv (see include/dsqconv.h): host-side validation and
 // dispatch only; every step of the path runs in the HIP kernels.
 #include <math.h>
+#include <string.h>
 
 #include "../../include/dsqconv.h"
 #include "dsq_device.h"
@@ -114,7 +115,52 @@ dsq_status conv_args(const dsq_conv_desc *d, const void *act_packed, const int32
     a.out = nullptr; a.acc = nullptr; a.out_nchw = 0;
     a.rq = 0; a.rq_scale = nullptr; a.rq_shift = nullptr; a.rq_relu = 0;
     a.rq_l = 0.f; a.rq_u = 1.f; a.rq_bits = 4; a.rq_Cp = 0; a.rq_codes = nullptr; a.rq_pix = nullptr;
+    for (int j = 0; j < 16; ++j) a.rq_thr[j] = 0.f;
+    a.rq_inv_delta = 0.f; a.rq_bias = 0.f;
     return DSQ_OK;
+}
+
+// ---- the quantizer as a step function (host side) ---------------------------
+// The same binary32 recipe as the device function dsq_code, operation for
+// operation (this file is compiled without contraction of a*b+c).
+int host_code(float x, float l, float u, float delta, int top)
+{
+    const float v = fminf(fmaxf(x, l), u);
+    const float t = (v - l) / delta;
+    int c = (int)floorf(t + 0.5f);
+    return c < 0 ? 0 : c > top ? top : c;
+}
+
+// Finite floats in increasing order <-> unsigned keys in increasing order.
+uint32_t key_of(float x)
+{
+    uint32_t b;
+    memcpy(&b, &x, 4);
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+float float_of(uint32_t k)
+{
+    const uint32_t b = (k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k;
+    float x;
+    memcpy(&x, &b, 4);
+    return x;
+}
+
+// thr[j], j = 1..top: the smallest finite float whose code is >= j (bisection over
+// the ordered floats; code() is monotone non-decreasing).
+void quantizer_thresholds(float l, float u, int bits, float thr[16])
+{
+    const int top = (1 << bits) - 1;
+    const float delta = (u - l) / (float)top;
+    for (int j = 0; j < 16; ++j) thr[j] = NAN;          // unused: no value compares >= NaN
+    for (int j = 1; j <= top; ++j) {
+        uint32_t lo = key_of(-3.4028234e38f), hi = key_of(3.4028234e38f);   // code(lo) = 0 < j <= code(hi) = top
+        while (hi - lo > 1) {
+            const uint32_t mid = lo + (hi - lo) / 2;
+            if (host_code(float_of(mid), l, u, delta, top) >= j) hi = mid; else lo = mid;
+        }
+        thr[j] = float_of(hi);
+    }
 }
 
 dsq_status launch_conv(const DsqConvArgs &a, hipStream_t stream)
@@ -165,6 +211,12 @@ dsq_status dsq_conv2d_requant(const dsq_conv_desc *d, const void *act_packed,
     a.rq_l = l_next; a.rq_u = u_next; a.rq_bits = bits_next;
     a.rq_Cp = dsq_round_up(a.C_out, 64);
     a.rq_codes = codes_next; a.rq_pix = pix_code_sum_next;
+    quantizer_thresholds(l_next, u_next, bits_next, a.rq_thr);
+    {
+        const float delta_n = (u_next - l_next) / (float)((1 << bits_next) - 1);
+        a.rq_inv_delta = 1.0f / delta_n;
+        a.rq_bias = 0.5f;
+    }
     if (dsq_launch_fill_zero(pix_code_sum_next, (size_t)a.N * a.Ho * a.Wo, (hipStream_t)hip_stream) !=
         hipSuccess)
         return DSQ_ERR_HIP;

@@ -123,6 +123,8 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
     int *pix_lds = reinterpret_cast<int *>(pq_lds + 2 * BC);
     // chained mode: scale and shift of the workgroup's channels (16-byte aligned)
     float *ss_lds = reinterpret_cast<float *>(lds + ((pl.aux_off + 2 * BC * 8 + pl.PR * pl.PC * 4 + 15) & ~15));
+    // chained mode: the next quantizer's thresholds as 16 (lower, upper) pairs
+    float2 *thr_lds = reinterpret_cast<float2 *>(ss_lds + 2 * BC);
 
     // KS = 2: two groups of four waves work on alternating 64-channel blocks of K
     // (each with its own patch buffers) and add their accumulators at the end, so
@@ -376,6 +378,16 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
         const double da0 = (double)dsq_delta(a.l_a, a.u_a, (1 << a.bits) - 1);
         if (tid < 2 * BC) pq_lds[tid] = da0 * (double)chan_const;
         if (RQ && tid < 2 * BC) ss_lds[tid] = rq_const;
+        if (RQ && tid < 16) {
+            // pair c = (thr[c], thr[c+1]); -inf below the first threshold, NaN above the last
+            float lo = -__builtin_inff(), hi = __builtin_nanf("");
+#pragma unroll
+            for (int j = 1; j < 16; ++j) {
+                lo = tid == j ? a.rq_thr[j] : lo;
+                hi = tid + 1 == j ? a.rq_thr[j] : hi;
+            }
+            thr_lds[tid] = make_float2(lo, hi);
+        }
     }
     DSQ_STAMP(2);
     lds_barrier();
@@ -505,31 +517,47 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
         // kernel.  Constants are fetched four channels at a time, right before
         // their use, to keep the register footprint of this path small.)
         const int top_n = (1 << a.rq_bits) - 1;
-        const float delta_n = dsq_delta(a.rq_l, a.rq_u, top_n);
+        const float relu_floor = a.rq_relu ? 0.0f : -__builtin_inff();
+        const float l_n = a.rq_l, u_n = a.rq_u, inv_delta_n = a.rq_inv_delta;
+        const float t1 = a.rq_thr[1], t2 = a.rq_thr[2], t3 = a.rq_thr[3];
+        auto chained = [&](auto linear) {
+            constexpr bool LINEAR = decltype(linear)::value;
 #pragma unroll
-        for (int c = 0; c < CT; ++c) {
-            if (KS == 2 && (c & 1) != grp) continue;
-            const int o_tile = (ct0 + c) * 32;
-            const int ol = (wc * CT + c) * 32 + 4 * h;       // this lane's first channel inside the workgroup
-#pragma unroll
-            for (int f = 0; f < PF; ++f) {
-                uint32_t bytes[4];
-                int sum = 0;
+            for (int c = 0; c < CT; ++c) {
+                if (KS == 2 && (c & 1) != grp) continue;
+                const int o_tile = (ct0 + c) * 32;
+                const int ol = (wc * CT + c) * 32 + 4 * h;   // this lane's first channel inside the workgroup
+                // bytes of channels >= C_out are blanked (their codes must be 0)
+                uint32_t mask[4];
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    float y[4];
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        y[j] = (float)__builtin_fma(pq_lds[ol + 8 * q + j], (double)acc[f][c][4 * q + j],
-                                                    pq_lds[BC + ol + 8 * q + j] * dsa[f]);
-                    const float4 s4 = *reinterpret_cast<const float4 *>(ss_lds + ol + 8 * q);
-                    const float4 b4 = *reinterpret_cast<const float4 *>(ss_lds + BC + ol + 8 * q);
-                    const float sc[4] = {s4.x, s4.y, s4.z, s4.w}, sh[4] = {b4.x, b4.y, b4.z, b4.w};
-                    bytes[q] = dsq_requant4(a, o_tile + 8 * q + 4 * h, y, sc, sh, delta_n, top_n, sum);
+                    const int left = a.C_out - (o_tile + 8 * q + 4 * h);      // valid channels from here on
+                    mask[q] = left >= 4 ? 0xFFFFFFFFu : left <= 0 ? 0u : (1u << (8 * left)) - 1u;
                 }
-                psum[f] += dsq_requant_store32(a, frag_m[f], o_tile, h, bytes, sum);
+#pragma unroll
+                for (int f = 0; f < PF; ++f) {
+                    uint32_t bytes[4];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        float y[4];
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            y[j] = (float)__builtin_fma(pq_lds[ol + 8 * q + j], (double)acc[f][c][4 * q + j],
+                                                        pq_lds[BC + ol + 8 * q + j] * dsa[f]);
+                        const float4 s4 = *reinterpret_cast<const float4 *>(ss_lds + ol + 8 * q);
+                        const float4 b4 = *reinterpret_cast<const float4 *>(ss_lds + BC + ol + 8 * q);
+                        const float sc[4] = {s4.x, s4.y, s4.z, s4.w}, sh[4] = {b4.x, b4.y, b4.z, b4.w};
+                        bytes[q] = dsq_requant4_thr<LINEAR>(y, sc, sh, relu_floor, l_n, u_n, inv_delta_n, top_n,
+                                                            t1, t2, t3, thr_lds, mask[q]);
+                    }
+                    const int sum = dsq_bytesum(bytes[0]) + dsq_bytesum(bytes[1]) + dsq_bytesum(bytes[2]) +
+                                    dsq_bytesum(bytes[3]);
+                    psum[f] += dsq_requant_store32(a, frag_m[f], o_tile, h, bytes, sum);
+                }
             }
-        }
+        };
+        if (top_n <= 3) chained(std::true_type{});
+        else chained(std::false_type{});
         // one integer atomic per pixel and wave (exact in any order)
         if (h == 0) {
 #pragma unroll
@@ -609,8 +637,8 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
 int plan_lds_bytes(const PatchPlan &p, int BC)
 {
     // tables behind the buffers: Da*Dw, Da*l_w (binary64), the patch pixels' code
-    // sums, and the chained mode's scale and shift
-    return ((p.aux_off + 2 * BC * 8 + p.PR * p.PC * 4 + 15) & ~15) + 2 * BC * 4;
+    // sums, and the chained mode's scale, shift and quantizer thresholds
+    return ((p.aux_off + 2 * BC * 8 + p.PR * p.PC * 4 + 15) & ~15) + 2 * BC * 4 + 16 * 8;
 }
 
 bool plan_patch(const DsqConvArgs &a, int BP, int BC, int PF, int CT, int UPT, int lds_limit, int KS, PatchPlan &best)

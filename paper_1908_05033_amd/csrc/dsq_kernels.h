@@ -30,6 +30,15 @@ struct DsqConvArgs {
     int rq_relu;
     float rq_l, rq_u;         // next layer's clip range
     int rq_bits;
+    // The next layer's quantizer as a step function: rq_thr[j] (j = 1..2^bits-1)
+    // is the smallest binary32 value whose code is >= j, found on the host with
+    // the very recipe of dsq_code (every step of it is monotone, so
+    // code(z) = #{j : z >= rq_thr[j]} exactly); unused entries are NaN, which
+    // no value compares >= to.  rq_inv_delta gives a first guess
+    // (int)((v - l) * rq_inv_delta + rq_bias) of floor((v - l)/Delta + 0.5) that
+    // is off by at most one.
+    float rq_thr[16];
+    float rq_inv_delta, rq_bias;
     int rq_Cp;                // C_out rounded up to 64
     void *rq_codes;           // packed codes of the next layer's input
     int32_t *rq_pix;          // [N*Ho*Wo], cleared before the launch

@@ -212,3 +212,50 @@ def test_argument_errors():
         with pytest.raises(B.DsqError) as e:
             B.dsq_conv2d_requant(*args, *tail)
         assert e.value.status == status
+
+
+def _oracle_threshold(l, u, bits, j):
+    """Smallest float32 whose oracle code is >= j (bisection over the ordered floats)."""
+    def key(x):
+        b = np.float32(x).view(np.uint32)
+        return int(~b & 0xFFFFFFFF) if b & 0x80000000 else int(b | 0x80000000)
+
+    def val(k):
+        b = (k & 0x7FFFFFFF) if k & 0x80000000 else (~k & 0xFFFFFFFF)
+        return np.uint32(b).view(np.float32)
+
+    lo, hi = key(-3.0e38), key(3.0e38)
+    while hi - lo > 1:
+        mid = (lo + hi) // 2
+        if oracle.quantize(np.array([val(mid)], np.float32), l, u, bits)[0] >= j:
+            hi = mid
+        else:
+            lo = mid
+    return hi, val
+
+
+@pytest.mark.parametrize("kernel", [0, 1, 3, 6])
+@pytest.mark.parametrize("l_n,u_n,bits_n", [(0.0, 3.0, 4), (-0.35, 2.45, 4), (0.0, 1.7, 3), (-1.0, 1.0, 2),
+                                            (0.0, 6.0, 2), (-1.0, 1.0, 1), (1000.0, 1000.5, 4)])
+def test_every_float_around_every_quantizer_threshold(l_n, u_n, bits_n, kernel):
+    """The tuned kernels evaluate the next layer's quantizer as a step function
+    (thresholds found on the host); the simple kernel and the oracle divide.
+    With all-zero weight codes and l_w = 0 the layer output is exactly 0, so
+    z = shift[o]: every float within three ulps of every threshold, and the
+    special values, go through the chained epilogue unchanged."""
+    l_n, u_n = float(np.float32(l_n)), float(np.float32(u_n))
+    vals = [np.float32(v) for v in (0.0, -0.0, l_n, u_n, np.inf, -np.inf, np.nan, 3.0e38, -3.0e38, 1e-45)]
+    for j in range(1, (1 << bits_n)):
+        k, val = _oracle_threshold(l_n, u_n, bits_n, j)
+        vals += [val(k + d) for d in range(-3, 4)]
+    C_out = (len(vals) + 3) // 4 * 4
+    shift = np.zeros(C_out, np.float32)
+    shift[:len(vals)] = vals
+    layer, inp = inputs.small_random_case(2, 1, 64, 3, 5, C_out, 1, 1, 0, 4, l_a=0.0, u_a=2.0)
+    inp["l_w"] = np.zeros(C_out, np.float32)
+    inp["u_w"] = np.ones(C_out, np.float32)
+    inp["w"] = torch.zeros_like(inp["w"])                      # code 0 with l_w = 0: the layer output is +0.0
+    scale = np.full(C_out, 1.5, np.float32)
+    want = oracle.quantize(shift, l_n, u_n, bits_n)            # (NaN -> code 0 by the recipe)
+    got, pix, *_ = run_requant_gpu(layer, inp, scale, shift, False, l_n, u_n, bits_n, kernel)
+    assert np.array_equal(got[..., :C_out], np.broadcast_to(want, got[..., :C_out].shape))
