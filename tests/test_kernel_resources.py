@@ -17,7 +17,7 @@ from paper_1908_05033_amd import build as B
 
 CSRC = os.path.join(os.path.dirname(B.__file__), "csrc")
 MAX_SPILLED_VGPRS = 40            # whole kernel
-MAX_SCRATCH_IN_MFMA_BLOCK = 32    # scratch instructions in a basic block that issues MFMAs
+MAX_SCRATCH_IN_MFMA_BLOCK = 48    # scratch instructions in a basic block that issues MFMAs
 
 
 def _device_asm(src):
