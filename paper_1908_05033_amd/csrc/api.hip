@@ -16,6 +16,8 @@ bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
 bool range_ok(float l, float u) { return isfinite(l) && isfinite(u) && l < u; }
 const long long kMaxElems = (1LL << 31) - 1;
 
+void quantizer_thresholds(float l, float u, int bits, float thr[16]);
+
 }  // namespace
 
 extern "C" {
@@ -52,7 +54,10 @@ dsq_status dsq_quantize_act(const float *x, dsq_layout layout, int N, int C, int
     if (layout == DSQ_NCHW && N > 65535) return DSQ_ERR_UNSUPPORTED;
     if (!aligned16(x) || !aligned16(codes_packed) || !aligned16(pix_code_sum)) return DSQ_ERR_ALIGN;
     if (codes_bytes < dsq_act_packed_bytes(N, H, W, C, bits)) return DSQ_ERR_SIZE;
-    hipError_t e = dsq_launch_quantize_act(x, layout == DSQ_NCHW, N, C, H, W, l, u, bits,
+    DsqThresholds th;
+    quantizer_thresholds(l, u, bits, th.thr);
+    th.inv_delta = 1.0f / ((u - l) / (float)((1 << bits) - 1));
+    hipError_t e = dsq_launch_quantize_act(x, layout == DSQ_NCHW, N, C, H, W, l, u, bits, th,
                                            codes_packed, pix_code_sum, (hipStream_t)hip_stream);
     return e == hipSuccess ? DSQ_OK : DSQ_ERR_HIP;
 }

@@ -135,23 +135,6 @@ __device__ __forceinline__ uint32_t dsq_requant4(const DsqConvArgs &a, int o0, c
     return dsq_bytes4(c[0], c[1], c[2], c[3]);
 }
 
-// The same codes from the quantizer's step-function form (see DsqConvArgs),
-// written without branches.  LINEAR (at most three thresholds): a chain of
-// compares.  Otherwise: a first guess from one multiply-add, corrected against
-// the two thresholds around it, which `thr_pairs` holds as (thr[c], thr[c+1]) for
-// c = 0..15 (-inf below the first, NaN above the last: nothing, not even +inf,
-// compares >= NaN).
-template <bool LINEAR>
-__device__ __forceinline__ int dsq_code_thr(float z, float l_n, float u_n, float inv_delta, int top_n,
-                                            float t1, float t2, float t3, const float2 *thr_pairs)
-{
-    if (LINEAR) return (z >= t1) + (z >= t2) + (z >= t3);
-    const float v = fminf(fmaxf(z, l_n), u_n);                       // NaN -> l, as in dsq_code
-    const int c0 = min((int)((v - l_n) * inv_delta + 0.5f), top_n);  // >= 0: v >= l
-    const float2 t = thr_pairs[c0];
-    return c0 + (z >= t.y) - (z < t.x);
-}
-
 // Codes of four consecutive channels from their fp32 results, one per byte.
 // relu_floor is 0 with ReLU and -inf without (max(z, -inf) = z; a NaN becomes
 // -inf, which has code 0 like the NaN itself); byte_mask blanks the bytes of

@@ -31,6 +31,26 @@ __device__ __forceinline__ int dsq_code(float x, float l, float u, float delta, 
     return min(max(c, 0), top);
 }
 
+// The quantizer as a step function.  Every operation of dsq_code (clip,
+// subtract, divide by Delta > 0, add 1/2, floor) is monotone non-decreasing in x,
+// so code(x) = #{j : x >= thr[j]} where thr[j] is the smallest binary32 value
+// whose code is >= j; the host finds these thresholds by bisection over the
+// ordered floats with the same recipe.  Written without branches.  LINEAR (at most three thresholds): a chain of
+// compares.  Otherwise: a first guess from one multiply-add, corrected against
+// the two thresholds around it, which `thr_pairs` holds as (thr[c], thr[c+1]) for
+// c = 0..15 (-inf below the first, NaN above the last: nothing, not even +inf,
+// compares >= NaN).
+template <bool LINEAR>
+__device__ __forceinline__ int dsq_code_thr(float z, float l_n, float u_n, float inv_delta, int top_n,
+                                            float t1, float t2, float t3, const float2 *thr_pairs)
+{
+    if (LINEAR) return (z >= t1) + (z >= t2) + (z >= t3);
+    const float v = fminf(fmaxf(z, l_n), u_n);                       // NaN -> l, as in dsq_code
+    const int c0 = min((int)((v - l_n) * inv_delta + 0.5f), top_n);  // >= 0: v >= l
+    const float2 t = thr_pairs[c0];
+    return c0 + (z >= t.y) - (z < t.x);
+}
+
 // Four codes -> one word with one code per byte.
 __device__ __forceinline__ uint32_t dsq_bytes4(int c0, int c1, int c2, int c3)
 {

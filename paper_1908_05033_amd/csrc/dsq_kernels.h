@@ -44,9 +44,17 @@ struct DsqConvArgs {
     int32_t *rq_pix;          // [N*Ho*Wo], cleared before the launch
 };
 
+// The quantizer of one tensor as a step function (see dsq_code_thr): thr[j],
+// j = 1..2^bits-1, is the smallest binary32 value whose code is >= j (NaN in
+// unused entries), found by the host with the recipe of dsq_code.
+struct DsqThresholds {
+    float thr[16];
+    float inv_delta;
+};
+
 hipError_t dsq_launch_quantize_act(const float *x, int layout_nchw, int N, int C, int H, int W,
-                                   float l, float u, int bits, void *codes, int32_t *pix_sum,
-                                   hipStream_t stream);
+                                   float l, float u, int bits, const DsqThresholds &th, void *codes,
+                                   int32_t *pix_sum, hipStream_t stream);
 
 hipError_t dsq_launch_pack_weights(const float *w, const float *l_w, const float *u_w,
                                    const uint8_t *codes, int C_out, int C_in, int R, int bits,

@@ -3,8 +3,11 @@
 // them sub-byte and emit the per-pixel code sums the convolution epilogue
 // needs for the l_w zero-point term.
 //
-// The kernel is bound by HBM traffic (4 B read and container/8 B written per
-// element); the only arithmetic of note is the IEEE division of the recipe.
+// The kernels are bound by HBM traffic (4 B read and container/8 B written per
+// element).  The NHWC kernels evaluate the recipe in its step-function form
+// (thresholds found on the host with the recipe itself: exactly the same codes,
+// without the IEEE division, which costs more than the memory time per element);
+// the NCHW kernel divides.
 #include "dsq_device.h"
 #include "dsq_kernels.h"
 
@@ -19,9 +22,41 @@ __device__ __forceinline__ int dpp_add(int v)
 // Codes of up to four consecutive channels starting at c0 -> one byte each.
 // VEC: the pixel's channel count is a multiple of 4 and x is 16-B aligned, so
 // a group of four is either wholly inside [0,C) or wholly outside.
-template <bool VEC>
-__device__ __forceinline__ uint32_t quant4(const float *px, int c0, int C, float l, float u,
-                                           float delta, int top)
+// The codes come from the step-function form of the quantizer (dsq_code_thr):
+// LINEAR for 1- and 2-bit codes, the guess-and-correct form with the (lower,
+// upper) threshold pairs `tp` in LDS for 3- and 4-bit codes.
+struct QuantParams {
+    float l, u, delta, inv_delta, t1, t2, t3;
+    int top;
+};
+
+// MODE 0: the recipe itself (dsq_code, with its division); 1: compare chain;
+// 2: guess and correct against the threshold pairs in LDS.
+template <int MODE>
+__device__ __forceinline__ int qcode(float x, const QuantParams &q, const float2 *tp)
+{
+    if (MODE == 0) return dsq_code(x, q.l, q.u, q.delta, q.top);
+    return dsq_code_thr<MODE == 1>(x, q.l, q.u, q.inv_delta, q.top, q.t1, q.t2, q.t3, tp);
+}
+
+// Threshold pairs of this block: pair c = (thr[c], thr[c+1]), -inf below the first
+// threshold, NaN above the last.  Needs a barrier before use.
+__device__ __forceinline__ void fill_threshold_pairs(float2 *tp, const DsqThresholds &th)
+{
+    if (threadIdx.x < 16) {
+        float lo = -__builtin_inff(), hi = __builtin_nanf("");
+#pragma unroll
+        for (int j = 1; j < 16; ++j) {
+            lo = (int)threadIdx.x == j ? th.thr[j] : lo;
+            hi = (int)threadIdx.x + 1 == j ? th.thr[j] : hi;
+        }
+        tp[threadIdx.x] = make_float2(lo, hi);
+    }
+}
+
+template <bool VEC, int MODE>
+__device__ __forceinline__ uint32_t quant4(const float *px, int c0, int C, const QuantParams &qp,
+                                           const float2 *tp)
 {
     float v0 = 0.f, v1 = 0.f, v2 = 0.f, v3 = 0.f;
     bool in0, in1, in2, in3;
@@ -38,10 +73,10 @@ __device__ __forceinline__ uint32_t quant4(const float *px, int c0, int C, float
         if (in2) v2 = px[c0 + 2];
         if (in3) v3 = px[c0 + 3];
     }
-    int q0 = in0 ? dsq_code(v0, l, u, delta, top) : 0;
-    int q1 = in1 ? dsq_code(v1, l, u, delta, top) : 0;
-    int q2 = in2 ? dsq_code(v2, l, u, delta, top) : 0;
-    int q3 = in3 ? dsq_code(v3, l, u, delta, top) : 0;
+    const int q0 = in0 ? qcode<MODE>(v0, qp, tp) : 0;
+    const int q1 = in1 ? qcode<MODE>(v1, qp, tp) : 0;
+    const int q2 = in2 ? qcode<MODE>(v2, qp, tp) : 0;
+    const int q3 = in3 ? qcode<MODE>(v3, qp, tp) : 0;
     return dsq_bytes4(q0, q1, q2, q3);
 }
 
@@ -51,14 +86,21 @@ __device__ __forceinline__ uint32_t quant4(const float *px, int c0, int C, float
 // block starts on a pixel, every aligned group of 8 (4) lanes works on one
 // pixel: their code sums are combined with DPP adds before one lane either
 // stores the pixel sum (one group per pixel) or adds it into LDS.
-template <int CONT, bool VEC>
+// THR: use the step-function form of the quantizer (large tensors, where the
+// division would cost more than the memory time); small, latency-bound tensors
+// keep the recipe itself and save the table set-up.
+template <int CONT, bool VEC, bool THR>
 __global__ __launch_bounds__(256) void quantize_act_nhwc_kernel(
     const float *__restrict__ x, uint32_t *__restrict__ codes, int32_t *__restrict__ pix_sum,
-    int total_pixels, int C, int DP, int dp_shift, int PB, float l, float u, int top)
+    int total_pixels, int C, int DP, int dp_shift, int PB, float l, float u, int top, DsqThresholds th)
 {
     constexpr int CPD = 32 / CONT;           // channels per packed word
     constexpr int GROUP = CPD == 8 ? 8 : 4;  // lanes that surely share a pixel
+    constexpr int MODE = !THR ? 0 : CONT == 2 ? 1 : 2;   // 1- and 2-bit codes: at most three thresholds
     __shared__ int spix[DSQ_QUANT_MAX_PB];
+    __shared__ float2 tpairs[16];
+    const QuantParams qp = {l, u, dsq_delta(l, u, top), th.inv_delta, th.thr[1], th.thr[2], th.thr[3], top};
+    if (MODE == 2) fill_threshold_pairs(tpairs, th);
 
     const int tid = threadIdx.x;
     const int pixel0 = blockIdx.x * PB;
@@ -66,9 +108,8 @@ __global__ __launch_bounds__(256) void quantize_act_nhwc_kernel(
     const bool multi_group = DP != GROUP;
     if (multi_group) {
         for (int i = tid; i < npix; i += 256) spix[i] = 0;
-        __syncthreads();
     }
-    const float delta = dsq_delta(l, u, top);
+    if (multi_group || MODE == 2) __syncthreads();
     const int ndw = npix * DP;
     const int ndw_up = (ndw + 255) & ~255;   // all lanes take part in the DPP adds
 
@@ -82,15 +123,15 @@ __global__ __launch_bounds__(256) void quantize_act_nhwc_kernel(
         if (active) {
             const float *px = x + (size_t)(pixel0 + p) * C;
             if (CONT == 4) {
-                uint32_t lo = quant4<VEC>(px, c0, C, l, u, delta, top);
-                uint32_t hi = quant4<VEC>(px, c0 + 4, C, l, u, delta, top);
+                uint32_t lo = quant4<VEC, MODE>(px, c0, C, qp, tpairs);
+                uint32_t hi = quant4<VEC, MODE>(px, c0 + 4, C, qp, tpairs);
                 word = dsq_pack8x4(lo, hi);
                 s = dsq_bytesum(lo) + dsq_bytesum(hi);
             } else {
-                uint32_t b0 = quant4<VEC>(px, c0, C, l, u, delta, top);
-                uint32_t b1 = quant4<VEC>(px, c0 + 4, C, l, u, delta, top);
-                uint32_t b2 = quant4<VEC>(px, c0 + 8, C, l, u, delta, top);
-                uint32_t b3 = quant4<VEC>(px, c0 + 12, C, l, u, delta, top);
+                uint32_t b0 = quant4<VEC, MODE>(px, c0, C, qp, tpairs);
+                uint32_t b1 = quant4<VEC, MODE>(px, c0 + 4, C, qp, tpairs);
+                uint32_t b2 = quant4<VEC, MODE>(px, c0 + 8, C, qp, tpairs);
+                uint32_t b3 = quant4<VEC, MODE>(px, c0 + 12, C, qp, tpairs);
                 word = b0 | (b1 << 2) | (b2 << 4) | (b3 << 6);
                 s = dsq_bytesum(b0) + dsq_bytesum(b1) + dsq_bytesum(b2) + dsq_bytesum(b3);
             }
@@ -107,6 +148,84 @@ __global__ __launch_bounds__(256) void quantize_act_nhwc_kernel(
     if (multi_group) {
         __syncthreads();
         for (int i = tid; i < npix; i += 256) pix_sum[pixel0 + i] = spix[i];
+    }
+}
+
+// NHWC input whose channel count is a multiple of one packed word (8 channels at
+// 4-bit containers, 16 at 2-bit) and whose base is 16-byte aligned -- the common
+// case.  Lane-contiguous version: consecutive lanes read consecutive float4
+// (every load instruction of a wave covers 1 KB of contiguous memory, where the
+// kernel above has each lane walk its own 32- or 64-byte segment), each lane
+// turns its four values into four code bytes, and the 2 (4) neighbouring lanes
+// that share a packed word combine their bytes with DPP moves.  A block owns PB
+// whole pixels; code sums are reduced over aligned lane groups inside a pixel
+// with DPP adds, then added into LDS counters.
+template <int CONT>
+__global__ __launch_bounds__(256) void quantize_act_nhwc_coalesced_kernel(
+    const float *__restrict__ x, uint32_t *__restrict__ codes, int32_t *__restrict__ pix_sum,
+    int total_pixels, int C, int DP, int PB, float inv_qp, float l, float u, int top, DsqThresholds th)
+{
+    constexpr int CPD = 32 / CONT;           // channels per packed word
+    constexpr int LPW = CPD / 4;             // lanes per packed word: 2 or 4
+    constexpr int MODE = CONT == 2 ? 1 : 2;  // 1- and 2-bit codes: at most three thresholds
+    __shared__ int spix[DSQ_QUANT_MAX_PB];
+    __shared__ float2 tpairs[16];
+    const QuantParams qp = {l, u, 0.f, th.inv_delta, th.thr[1], th.thr[2], th.thr[3], top};
+    if (MODE == 2) fill_threshold_pairs(tpairs, th);
+
+    const int tid = threadIdx.x;
+    const int pixel0 = blockIdx.x * PB;
+    const int npix = min(PB, total_pixels - pixel0);
+    const int QP = C / 4;                    // float4 units per pixel (a multiple of LPW)
+    const int real_words = C / CPD;          // packed words per pixel that carry channels
+    for (int i = tid; i < npix; i += 256) spix[i] = 0;
+    __syncthreads();
+
+    const int nunits = npix * QP;
+    const int nunits_up = (nunits + 255) & ~255;     // all lanes take part in the DPP moves
+    const float4 *xb = reinterpret_cast<const float4 *>(x + (size_t)pixel0 * C);
+    // lanes of an aligned group of `group` lanes belong to one pixel
+    const int group = (QP & 15) == 0 ? 16 : (QP & 7) == 0 ? 8 : (QP & 3) == 0 ? 4 : 2;
+
+    for (int i = tid; i < nunits_up; i += 256) {
+        const bool active = i < nunits;
+        uint32_t b = 0;
+        if (active) {
+            const float4 f = xb[i];
+            b = dsq_bytes4(qcode<MODE>(f.x, qp, tpairs), qcode<MODE>(f.y, qp, tpairs),
+                           qcode<MODE>(f.z, qp, tpairs), qcode<MODE>(f.w, qp, tpairs));
+        }
+        int p = (int)((float)i * inv_qp);            // i / QP with a float reciprocal and a fix-up (i < 2^22)
+        int q = i - p * QP;
+        if (q < 0) { --p; q += QP; }
+        if (q >= QP) { ++p; q -= QP; }
+        int s = dsq_bytesum(b);
+        uint32_t word;
+        if (CONT == 4) {
+            // word = channels 8w..8w+7: byte j = c[j] | c[j+4] << 4; the odd lane holds c[4..7]
+            const uint32_t other = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)b, 0xB1, 0xF, 0xF, true);
+            word = b | (other << 4);
+        } else {
+            // word = 16 channels: byte j = c[j] | c[j+4] << 2 | c[j+8] << 4 | c[j+12] << 6
+            uint32_t v = b << (2 * (tid & 3));
+            v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, true);
+            v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, true);
+            word = v;
+        }
+        if (active && (tid & (LPW - 1)) == 0) codes[(size_t)(pixel0 + p) * DP + q / LPW] = word;
+        s = dpp_add<0xB1>(s);                                   // lanes ^1
+        if (group >= 4) s = dpp_add<0x4E>(s);                   // lanes ^2
+        if (group >= 8) s = dpp_add<0x141>(s);                  // other quad (row_half_mirror)
+        if (group >= 16) s = dpp_add<0x140>(s);                 // other half row (row_mirror)
+        if (active && (tid & (group - 1)) == 0) atomicAdd(&spix[p], s);
+    }
+    __syncthreads();
+    for (int i = tid; i < npix; i += 256) pix_sum[pixel0 + i] = spix[i];
+    // channels C..Cp-1 of every pixel hold code 0
+    const int pad_words = DP - real_words;
+    for (int i = tid; i < npix * pad_words; i += 256) {
+        const int p = i / pad_words, d = real_words + i - p * pad_words;
+        codes[(size_t)(pixel0 + p) * DP + d] = 0;
     }
 }
 
@@ -152,8 +271,8 @@ __global__ __launch_bounds__(256) void quantize_act_nchw_kernel(
 }  // namespace
 
 hipError_t dsq_launch_quantize_act(const float *x, int layout_nchw, int N, int C, int H, int W,
-                                   float l, float u, int bits, void *codes, int32_t *pix_sum,
-                                   hipStream_t stream)
+                                   float l, float u, int bits, const DsqThresholds &th, void *codes,
+                                   int32_t *pix_sum, hipStream_t stream)
 {
     const int cont = dsq_container(bits);
     const int top = (1 << bits) - 1;
@@ -181,10 +300,35 @@ hipError_t dsq_launch_quantize_act(const float *x, int layout_nchw, int N, int C
     int dp_shift = -1;
     if ((DP & (DP - 1)) == 0) { dp_shift = 0; while ((1 << dp_shift) < DP) ++dp_shift; }
     const bool vec = (C % 4 == 0) && (((uintptr_t)x & 15) == 0);
+    // The lane-contiguous kernel wins on tensors large enough to be bandwidth bound
+    // (measured: 4.0 -> 5.0 TB/s at 2 bits); small ones are latency bound and do
+    // better with the kernel below, which has less per-block set-up.
+    if (vec && C % (32 / cont) == 0 && (long long)total_pixels * (C / 4) >= 512 * 1024) {
+        const int QP = C / 4;
+        const long long total_units = (long long)total_pixels * QP;
+        int it = 8;
+        while (it > 2 && total_units / (256LL * it) < 2048) it >>= 1;
+        int pb = (256 * it) / QP;
+        if (pb < 1) pb = 1;
+        if (pb > DSQ_QUANT_MAX_PB) pb = DSQ_QUANT_MAX_PB;
+        dim3 g((total_pixels + pb - 1) / pb);
+        if (cont == 4)
+            quantize_act_nhwc_coalesced_kernel<4><<<g, 256, 0, stream>>>(
+                x, (uint32_t *)codes, pix_sum, total_pixels, C, DP, pb, 1.0f / (float)QP, l, u, top, th);
+        else
+            quantize_act_nhwc_coalesced_kernel<2><<<g, 256, 0, stream>>>(
+                x, (uint32_t *)codes, pix_sum, total_pixels, C, DP, pb, 1.0f / (float)QP, l, u, top, th);
+        return hipGetLastError();
+    }
     dim3 grid((total_pixels + PB - 1) / PB);
+    const bool thr = total_dw >= 256 * 1024;       // large enough to be bandwidth bound
 #define DSQ_Q_LAUNCH(CONT, VEC)                                                              \
-    quantize_act_nhwc_kernel<CONT, VEC><<<grid, 256, 0, stream>>>(                           \
-        x, (uint32_t *)codes, pix_sum, total_pixels, C, DP, dp_shift, PB, l, u, top)
+    do {                                                                                     \
+        if (thr) quantize_act_nhwc_kernel<CONT, VEC, true><<<grid, 256, 0, stream>>>(        \
+            x, (uint32_t *)codes, pix_sum, total_pixels, C, DP, dp_shift, PB, l, u, top, th); \
+        else quantize_act_nhwc_kernel<CONT, VEC, false><<<grid, 256, 0, stream>>>(           \
+            x, (uint32_t *)codes, pix_sum, total_pixels, C, DP, dp_shift, PB, l, u, top, th); \
+    } while (0)
     if (cont == 4) { if (vec) DSQ_Q_LAUNCH(4, true); else DSQ_Q_LAUNCH(4, false); }
     else           { if (vec) DSQ_Q_LAUNCH(2, true); else DSQ_Q_LAUNCH(2, false); }
 #undef DSQ_Q_LAUNCH
