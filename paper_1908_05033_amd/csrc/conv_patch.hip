@@ -801,7 +801,7 @@ bool choose_plan(const DsqConvArgs &a, int force_tile, int &which, int &ks, Patc
     const int BP = 32 * tc.PF * tc.WP, BC = 32 * tc.CT * tc.WC;
     const long long M = (long long)a.N * a.Ho * a.Wo;
     const long long blocks = ((M + BP - 1) / BP) * ((a.C_out + BC - 1) / BC);
-    ks = (which == TILE_SMALL && a.Cp >= 128 && blocks <= 320) ? 2 : 1;
+    ks = ((which == TILE_SMALL || which == TILE_MEDIUM) && a.Cp >= 128 && blocks <= 320) ? 2 : 1;
     if (ks == 2 && plan_patch(a, BP, BC, tc.PF, tc.CT, kMaxUPT, kLdsLimit, 2, pl)) return true;
     ks = 1;
     return plan_patch(a, BP, BC, tc.PF, tc.CT, kMaxUPT, kLdsLimit, 1, pl);
@@ -826,6 +826,7 @@ hipError_t dsq_launch_conv_patch(const DsqConvArgs &a, int force_tile, hipStream
 #define DSQ_TILE(CONT, RR, UPT)                                                                \
     do {                                                                                       \
         if (which == TILE_LARGE) return launch_kernel<CONT, RR, 2, 2, 4, 2, UPT, (RR == 3 ? 3 : 1), 2, 1, false>(a, pl, stream);  \
+        if (which == TILE_MEDIUM && ks == 2) return launch_cfg<CONT, RR, 2, 2, 2, 2, UPT, (RR == 3 ? 3 : 1), 2, 2>(a, pl, stream); \
         if (which == TILE_MEDIUM) return launch_cfg<CONT, RR, 2, 2, 2, 2, UPT, (RR == 3 ? 3 : 1), 3>(a, pl, stream); \
         if (which == TILE_TALL) return launch_cfg<CONT, RR, 4, 1, 2, 2, UPT, (RR == 3 ? 3 : 1), 3>(a, pl, stream); \
         if (ks == 2) return launch_cfg<CONT, RR, 4, 1, 1, 2, UPT, (RR == 3 ? 3 : 1), 2, 2>(a, pl, stream); \
