@@ -120,3 +120,37 @@ def test_kernel_selector_roundtrip():
     assert B.dsq_set_conv_kernel(99) == prev      # out of range: unchanged
     assert B.dsq_set_conv_kernel(-1) == prev
     assert B.dsq_set_conv_kernel(prev) == prev
+
+
+def _r(desc=None, act=FAKE, pix=FAKE, la=0.0, ua=1.0, wp=FAKE, aux=FAKE, scale=None, shift=None, relu=1,
+       ln=0.0, un=1.0, bn=4, codes=FAKE, nbytes=1 << 20, pixn=FAKE, **kw):
+    d = dict(N=1, C_in=8, H=4, W=4, C_out=8, R=3, S=3, stride=1, pad=1, bits=4)
+    d.update(kw)
+    desc = B.dsq_conv_desc(**d) if desc is None else desc
+    return B.load_library().dsq_conv2d_requant(C.byref(desc), act, pix, la, ua, wp, aux, scale, shift, relu,
+                                               ln, un, bn, codes, nbytes, pixn, None)
+
+
+def test_conv2d_requant_rejects_bad_arguments():
+    assert _r(codes=None) == 1 and _r(pixn=None) == 1 and _r(act=None) == 1
+    assert _r(bn=0) == 2 and _r(bn=5) == 2 and _r(bits=9) == 2
+    assert _r(ln=1.0, un=1.0) == 3 and _r(un=float("inf")) == 3 and _r(la=2.0, ua=1.0) == 3
+    assert _r(C_out=0) == 4
+    assert _r(stride=4) == 5
+    assert _r(codes=FAKE + 8) == 6 and _r(scale=FAKE + 4) == 6 and _r(shift=FAKE + 12) == 6
+    assert _r(nbytes=16 * 32 - 1) == 7            # 16 pixels x 64 padded channels x 4 bits
+
+
+def test_soft_quantize_rejects_bad_arguments():
+    lib = B.load_library()
+    fwd = lambda x=FAKE, n=16, l=0.0, u=1.0, a=0.2, b=4, y=FAKE: lib.dsq_soft_quantize_fwd(x, n, l, u, a, b, y, None)
+    bwd = lambda x=FAKE, g=FAKE, n=16, l=0.0, u=1.0, a=0.2, b=4, gx=FAKE, s=FAKE: \
+        lib.dsq_soft_quantize_bwd(x, g, n, l, u, a, b, gx, s, None)
+    assert fwd(x=None) == 1 and fwd(y=None) == 1
+    assert fwd(b=0) == 2 and fwd(b=5) == 2
+    assert fwd(a=0.0) == 3 and fwd(a=0.5) == 3 and fwd(a=float("nan")) == 3 and fwd(l=1.0, u=0.5) == 3
+    assert fwd(n=0) == 4 and fwd(n=1 << 31) == 4
+    assert fwd(x=FAKE + 4) == 6
+    assert bwd(g=None) == 1 and bwd(s=None) == 1 and bwd(gx=None) == 1
+    assert bwd(a=0.7) == 3 and bwd(b=7) == 2 and bwd(n=0) == 4
+    assert bwd(s=FAKE + 8) == 6 and bwd(g=FAKE + 4) == 6
