@@ -24,7 +24,11 @@
  *   - Arguments are validated on the host before anything is launched; on any
  *     error nothing has been enqueued.  Errors are return codes only.
  *   - Device pointers must be 16-byte aligned.
- *   - bits is 1, 2, 3 or 4, the same for activations and weights of one layer.
+ *   - bits is 1, 2, 3 or 4.  The descriptor's bits is the activations' width; the
+ *     weights may have been packed with another width of the same container
+ *     class ({1,2} or {3,4}, e.g. 3-bit weights under 4-bit activations): their
+ *     step travels in w_aux.  Widths of different container classes in one
+ *     layer are not supported.
  *     bits = 1 is the binary case of Sec. 3.1: with (l, u) = (-1, +1) the two
  *     levels are sgn(x) (code 1 for x >= 0), and any other (l, u) gives the
  *     two-level quantizer with levels l and u.
