@@ -696,7 +696,10 @@ bool plan_patch(const DsqConvArgs &a, int BP, int BC, int PF, int CT, int UPT, i
         p.inv_PC = 1.0f / (float)p.PC; p.inv_tiles_w = 1.0f / (float)tiles_w;
         p.step_q = (256 / UPP) / p.PC;
         p.step_r = (256 / UPP) % p.PC;
-        p.aux_off = 2 * KS * p.buf_bytes > epi_bytes ? 2 * KS * p.buf_bytes : epi_bytes;
+        // a layer whose wave groups each see a single stage never touches the second
+        // buffer of a group: leave it out, so that more workgroups fit a CU
+        const int nbuf = a.Cp / 64 > KS ? 2 : 1;
+        p.aux_off = nbuf * KS * p.buf_bytes > epi_bytes ? nbuf * KS * p.buf_bytes : epi_bytes;
         if (plan_lds_bytes(p, BC) > lds_limit) continue;
         if (p.units > 256 * UPT) continue;
         const long long tiles = (long long)p.tiles_w * p.row_tiles;
