@@ -138,6 +138,19 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
     const int col = lane & 31, h = lane >> 5;
     const int wp = wave % WP, wc = wave / WP;
 
+    // The kernel arguments live in memory that is slow to reach.  Naming all of
+    // them as scalar-register inputs of an (empty) asm statement right here makes
+    // the compiler fetch them in one batch at the top of the kernel -- one round
+    // trip instead of one per group of first uses -- at no instruction cost.
+    asm volatile("" ::"s"(a.N), "s"(a.C_in), "s"(a.H), "s"(a.W), "s"(a.C_out), "s"(a.stride), "s"(a.pad),
+                 "s"(a.bits), "s"(a.Ho), "s"(a.Wo), "s"(a.Cp), "s"(a.out_nchw), "s"(a.R), "s"(a.Cop),
+                 "s"(a.l_a), "s"(a.u_a), "s"(a.act), "s"(a.pix_sum), "s"(a.wq), "s"(a.delta_w), "s"(a.l_w),
+                 "s"(a.out), "s"(a.acc));
+    asm volatile("" ::"s"(pl.TW), "s"(pl.BP), "s"(pl.tiles_w), "s"(pl.PR), "s"(pl.PC), "s"(pl.RP),
+                 "s"(pl.buf_bytes), "s"(pl.Hp), "s"(pl.aux_off), "s"(pl.step_q), "s"(pl.step_r),
+                 "s"(pl.tiles_c), "s"(pl.total_blocks), "s"(pl.xcd_chunk), "s"(pl.inv_tiles_c), "s"(pl.inv_PC),
+                 "s"(pl.inv_TW), "s"(pl.inv_Hp), "s"(pl.inv_Ho), "s"(pl.inv_tiles_w));
+
     // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Give
     // every XCD a contiguous range of tiles, channel tiles of one pixel tile
     // first, so that the tiles that share activations (same pixels, halo rows of
@@ -147,23 +160,6 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
     int blk_y;
     const int blk_x = fdiv(logical, pl.tiles_c, pl.inv_tiles_c, blk_y);
     DSQ_STAMP(0);
-
-    // The kernel arguments live in memory that is slow to reach; touching all of
-    // them here makes the compiler fetch them in one batch instead of one
-    // round trip per group of first uses.  (The test cannot be true: N >= 1.)
-    {
-        const long long touch =
-            (long long)a.N + a.C_in + a.H + a.W + a.C_out + a.stride + a.pad + a.bits + a.Ho + a.Wo + a.Cp +
-            (long long)(a.out_nchw & 1) + (long long)(intptr_t)a.act + (long long)(intptr_t)a.pix_sum +
-            (long long)(intptr_t)a.wq + (long long)(intptr_t)a.delta_w + (long long)(intptr_t)a.l_w +
-            (long long)(intptr_t)a.out + (long long)(intptr_t)a.acc + (long long)(intptr_t)a.sw_total +
-            (long long)(intptr_t)a.sw_tap + a.R + a.Cop + pl.TW + pl.BP + pl.tiles_w + pl.PR + pl.PC +
-            pl.RP + pl.buf_bytes + pl.Hp + pl.units + pl.aux_off + pl.step_q + pl.step_r + pl.tiles_c +
-            pl.total_blocks + pl.xcd_chunk + __float_as_int(pl.inv_tiles_c) +
-            (long long)__float_as_int(pl.inv_PC) + __float_as_int(pl.inv_TW) + __float_as_int(pl.inv_Hp) +
-            __float_as_int(pl.inv_Ho) + __float_as_int(pl.inv_tiles_w) + __float_as_int(a.l_a) + __float_as_int(a.u_a);
-        if (a.N == 0 && touch == 0x7FFFFFFFFFFFFFFFLL) return;
-    }
 
     const int NCB = a.Cp / 64;
     const int NHo = a.N * a.Ho;
