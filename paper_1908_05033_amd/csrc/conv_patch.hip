@@ -138,6 +138,9 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
     const int col = lane & 31, h = lane >> 5;
     const int wp = wave % WP, wc = wave / WP;
 
+#ifdef DSQ_TRACE
+    const unsigned long long dsq_t_begin = __builtin_amdgcn_s_memtime();
+#endif
     // The kernel arguments live in memory that is slow to reach.  Naming all of
     // them as scalar-register inputs of an (empty) asm statement right here makes
     // the compiler fetch them in one batch at the top of the kernel -- one round
@@ -160,6 +163,9 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
     int blk_y;
     const int blk_x = fdiv(logical, pl.tiles_c, pl.inv_tiles_c, blk_y);
     DSQ_STAMP(0);
+#ifdef DSQ_TRACE
+    if (lane == 0 && blk_y == 0 && blk_x < 512) dsq_trace_buf[(blk_x * 8 + grp * 4 + wave) * 32 + 11] = dsq_t_begin;
+#endif
 
     const int NCB = a.Cp / 64;
     const int NHo = a.N * a.Ho;
@@ -262,11 +268,11 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
     int pix_val[UPT];
 #pragma unroll
     for (int k = 0; k < UPT; ++k) pix_val[k] = a.pix_sum[src_pix[k]];
-    float chan_const = 0.f;
-    if (grp == 0 && tid < 2 * BC) {
-        const int o = blk_y * BC + (tid < BC ? tid : tid - BC);      // < Cop by construction
-        chan_const = tid < BC ? a.delta_w[o] : a.l_w[o];
-    }
+    // (every lane loads an entry, used or not: a load under a branch would drag
+    // the wait for it, and for everything issued before it, up to this point)
+    const int chan_i = tid < 2 * BC ? tid : 0;
+    const int chan_o = blk_y * BC + (chan_i < BC ? chan_i : chan_i - BC);      // < Cop by construction
+    const float chan_const = (chan_i < BC ? a.delta_w : a.l_w)[chan_o];
     float rq_const = 0.f;
     if (RQ && grp == 0 && tid < 2 * BC) {
         const int o = blk_y * BC + (tid < BC ? tid : tid - BC);
@@ -316,6 +322,11 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
 #pragma unroll
             for (int kh = 0; kh < KH; ++kh)
                 af[0][f][kh] = *reinterpret_cast<const v4i *>(buf + frag_off[f] + 32 * kh);
+        // (keep these LDS reads first in the stage: their latency then runs under the
+        // unpacking of the first weight fragments instead of in front of the first MFMA.
+        // Only where registers are plentiful: the one-group variants spill under
+        // this constraint.)
+        if constexpr (KS == 2) __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int t = 0; t < T; ++t) {
             if (t + 1 < T) {
@@ -362,6 +373,17 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
     // patch buffers: [parity][group]
     auto patch_buf = [&](int parity) { return lds + (parity * KS + grp) * pl.buf_bytes; };
     DSQ_STAMP(1);
+    // (have the fragment offsets computed here, under the latency of the patch
+    // fetch, rather than after the barrier where nothing hides them)
+#pragma unroll
+    for (int f = 0; f < PF; ++f) asm volatile("" ::"v"(frag_off[f]), "v"(frag_pp[f]), "v"(frag_m[f]));
+    // (likewise the zeroing of the accumulators, where registers are plentiful)
+    if constexpr (KS == 2) {
+#pragma unroll
+        for (int f = 0; f < PF; ++f)
+#pragma unroll
+            for (int c = 0; c < CT; ++c) asm volatile("" : "+v"(macc[f][c]));
+    }
     store_patch(patch_buf(0));
     if (grp == 0) {
         int pp = UPP == 2 ? (tid >> 1) : tid;
