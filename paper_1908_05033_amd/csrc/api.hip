@@ -112,6 +112,8 @@ dsq_status conv_args(const dsq_conv_desc *d, const void *act_packed, const int32
     a.stride = d->stride; a.pad = d->pad; a.bits = d->bits;
     a.Ho = Ho; a.Wo = Wo; a.Cp = Cp; a.Cop = Cop;
     a.act = act_packed; a.pix_sum = pix_code_sum; a.l_a = l_a; a.u_a = u_a;
+    // (one IEEE binary32 subtraction and division: the value dsq_delta gives on the device)
+    a.delta_a = (u_a - l_a) / (float)((1 << d->bits) - 1);
     a.wq = w_packed;
     a.delta_w = (const float *)w_aux;
     a.l_w = a.delta_w + Cop;

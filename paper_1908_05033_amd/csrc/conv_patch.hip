@@ -65,9 +65,9 @@ struct PatchPlan {
     int tiles_c;       // channel tiles (workgroups per pixel tile)
     int total_blocks;  // pixel tiles * channel tiles
     int xcd_chunk;     // ceil(total_blocks / 8)
-    float inv_tiles_c;
+    uint32_t mg_tiles_c;   // division constants (see idiv) of tiles_c ...
     int step_q, step_r;   // (256 / units-per-pixel) divided by PC: quotient and remainder
-    float inv_PC, inv_TW, inv_Hp, inv_Ho, inv_tiles_w;   // reciprocals for the index divisions
+    uint32_t mg_PC, mg_TW, mg_Hp, mg_Ho, mg_tiles_w;   // ... and of PC, TW, Hp, Ho, tiles_w
 };
 
 // Workgroup barrier that orders LDS traffic only.  __syncthreads() also drains
@@ -78,12 +78,14 @@ __device__ __forceinline__ void lds_barrier()
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
-// x / d for 0 <= x < 2^22 and d >= 1, with a float reciprocal and a fix-up.
-__device__ __forceinline__ int fdiv(int x, int d, float inv_d, int &rem)
+// x / d for x >= 0 and d >= 1 by multiplication: with m = min(floor(2^32 / d), 2^32 - 1)
+// (computed on the host, division_constant below) the high word of x * m is the
+// quotient or one less, so one correction suffices.  Wave-uniform operands stay
+// on the scalar unit.
+__device__ __forceinline__ int idiv(int x, int d, uint32_t m, int &rem)
 {
-    int q = (int)((float)x * inv_d);
+    int q = (int)__umulhi((uint32_t)x, m);
     int r = x - q * d;
-    if (r < 0) { --q; r += d; }
     if (r >= d) { ++q; r -= d; }
     rem = r;
     return q;
@@ -147,12 +149,12 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
     // trip instead of one per group of first uses -- at no instruction cost.
     asm volatile("" ::"s"(a.N), "s"(a.C_in), "s"(a.H), "s"(a.W), "s"(a.C_out), "s"(a.stride), "s"(a.pad),
                  "s"(a.bits), "s"(a.Ho), "s"(a.Wo), "s"(a.Cp), "s"(a.out_nchw), "s"(a.R), "s"(a.Cop),
-                 "s"(a.l_a), "s"(a.u_a), "s"(a.act), "s"(a.pix_sum), "s"(a.wq), "s"(a.delta_w), "s"(a.l_w),
+                 "s"(a.l_a), "s"(a.u_a), "s"(a.delta_a), "s"(a.act), "s"(a.pix_sum), "s"(a.wq), "s"(a.delta_w), "s"(a.l_w),
                  "s"(a.out), "s"(a.acc));
     asm volatile("" ::"s"(pl.TW), "s"(pl.BP), "s"(pl.tiles_w), "s"(pl.PR), "s"(pl.PC), "s"(pl.RP),
                  "s"(pl.buf_bytes), "s"(pl.Hp), "s"(pl.aux_off), "s"(pl.step_q), "s"(pl.step_r),
-                 "s"(pl.tiles_c), "s"(pl.total_blocks), "s"(pl.xcd_chunk), "s"(pl.inv_tiles_c), "s"(pl.inv_PC),
-                 "s"(pl.inv_TW), "s"(pl.inv_Hp), "s"(pl.inv_Ho), "s"(pl.inv_tiles_w));
+                 "s"(pl.tiles_c), "s"(pl.total_blocks), "s"(pl.xcd_chunk), "s"(pl.mg_tiles_c), "s"(pl.mg_PC),
+                 "s"(pl.mg_TW), "s"(pl.mg_Hp), "s"(pl.mg_Ho), "s"(pl.mg_tiles_w));
 
     // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Give
     // every XCD a contiguous range of tiles, channel tiles of one pixel tile
@@ -161,7 +163,7 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
     const int logical = ((int)blockIdx.x & 7) * pl.xcd_chunk + ((int)blockIdx.x >> 3);
     if (logical >= pl.total_blocks) return;
     int blk_y;
-    const int blk_x = fdiv(logical, pl.tiles_c, pl.inv_tiles_c, blk_y);
+    const int blk_x = idiv(logical, pl.tiles_c, pl.mg_tiles_c, blk_y);
     DSQ_STAMP(0);
 #ifdef DSQ_TRACE
     if (lane == 0 && blk_y == 0 && blk_x < 512) dsq_trace_buf[(blk_x * 8 + grp * 4 + wave) * 32 + 11] = dsq_t_begin;
@@ -195,13 +197,13 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
 
     // ---- tile position -------------------------------------------------------
     int tile_w;
-    const int tile_r = fdiv(blk_x, pl.tiles_w, pl.inv_tiles_w, tile_w);
+    const int tile_r = idiv(blk_x, pl.tiles_w, pl.mg_tiles_w, tile_w);
     const int t0 = tile_r * pl.BP;              // first pixel of the tile, numbered inside the strip
     const int ow0 = tile_w * pl.TW;
     int tc0;
-    const int gr0 = fdiv(t0, pl.TW, pl.inv_TW, tc0);   // its output row (batch-wide numbering)
+    const int gr0 = idiv(t0, pl.TW, pl.mg_TW, tc0);   // its output row (batch-wide numbering)
     int oh0;
-    const int n0 = fdiv(gr0, a.Ho, pl.inv_Ho, oh0);
+    const int n0 = idiv(gr0, a.Ho, pl.mg_Ho, oh0);
     const int v0 = n0 * pl.Hp + oh0 * a.stride;   // first padded input row of the patch
     const int vc0 = ow0 * a.stride;               // first padded input column of the patch
     const uint32_t row_bytes = (uint32_t)a.Cp * CONT / 8;
@@ -217,8 +219,8 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
     const int half = UPP == 2 ? (tid & 1) : 0;
     {
         int pcol, ihp;
-        int prow = fdiv(UPP == 2 ? (tid >> 1) : tid, pl.PC, pl.inv_PC, pcol);
-        int n = fdiv(v0 + prow, pl.Hp, pl.inv_Hp, ihp);
+        int prow = idiv(UPP == 2 ? (tid >> 1) : tid, pl.PC, pl.mg_PC, pcol);
+        int n = idiv(v0 + prow, pl.Hp, pl.mg_Hp, ihp);
 #pragma unroll
         for (int k = 0; k < UPT; ++k) {
             const int ih = ihp - a.pad, iw = vc0 + pcol - a.pad;
@@ -290,13 +292,13 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
     for (int f = 0; f < PF; ++f) {
         const int t = t0 + (wp * PF + f) * 32 + col;
         int tc;
-        const int gr = fdiv(t, pl.TW, pl.inv_TW, tc);
+        const int gr = idiv(t, pl.TW, pl.mg_TW, tc);
         const int ow = ow0 + tc;
         const bool ok = gr < NHo && ow < a.Wo;
         int prow = 0, pcol = 0;
         if (ok) {
             int oh;
-            const int n = fdiv(gr, a.Ho, pl.inv_Ho, oh);
+            const int n = idiv(gr, a.Ho, pl.mg_Ho, oh);
             prow = n * pl.Hp + oh * a.stride - v0;
             pcol = tc * a.stride;
         }
@@ -393,7 +395,7 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
             pp += 256 / UPP;
         }
         // Da*Dw[o] and Da*l_w[o] of this workgroup's channels, in binary64
-        const double da0 = (double)dsq_delta(a.l_a, a.u_a, (1 << a.bits) - 1);
+        const double da0 = (double)a.delta_a;
         if (tid < 2 * BC) pq_lds[tid] = da0 * (double)chan_const;
         if (RQ && tid < 2 * BC) ss_lds[tid] = rq_const;
         if (RQ && tid < 16) {
@@ -424,7 +426,7 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
     }
     // ---- side values of the epilogue (see conv_epilogue.h for the algebra) ------
     const int top = (1 << a.bits) - 1;
-    const float delta_a = dsq_delta(a.l_a, a.u_a, top);
+    const float delta_a = a.delta_a;
     // fast path: NHWC fp32 output only, l_a = 0, C_out a multiple of 4
     const bool fast = !a.out_nchw && (a.C_out & 3) == 0 && a.l_a == 0.0f && a.acc == nullptr;
     // per fragment: SA = code sums of the patch pixels under the taps (0 in the padding)
@@ -660,6 +662,13 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
 
 // ---- host side: tile planning and dispatch ---------------------------------
 
+// m of idiv() for the divisor d >= 1
+uint32_t division_constant(int d)
+{
+    const unsigned long long m = (1ull << 32) / (unsigned long long)d;
+    return m > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)m;
+}
+
 // Picks the strip width TW minimising padded work, then patch size.
 int plan_lds_bytes(const PatchPlan &p, int BC)
 {
@@ -686,7 +695,7 @@ bool plan_patch(const DsqConvArgs &a, int BP, int BC, int PF, int CT, int UPT, i
         p.TW = TW; p.BP = BP; p.Hp = Hp;
         p.tiles_w = tiles_w;
         const long long strip_pixels = (long long)NHo * TW;
-        if (strip_pixels + BP >= (1 << 22)) continue;          // fdiv operand range
+        if (strip_pixels + BP >= (1 << 22)) continue;          // keeps every index well inside 32 bits
         p.row_tiles = (int)((strip_pixels + BP - 1) / BP);
         p.PC = (TW - 1) * a.stride + a.R;
         // patch rows: padded-row span of the tile's output rows, worst tile
@@ -710,8 +719,8 @@ bool plan_patch(const DsqConvArgs &a, int BP, int BC, int PF, int CT, int UPT, i
         p.RP = p.PC * PIX_STRIDE + (a.stride == 1 ? skew : 0);
         p.buf_bytes = (p.PR * p.RP + 64 + 255) & ~255;   // + dump slot for idle fetch units
         p.units = p.PR * p.PC * UPP;
-        p.inv_TW = 1.0f / (float)TW; p.inv_Hp = 1.0f / (float)Hp; p.inv_Ho = 1.0f / (float)a.Ho;
-        p.inv_PC = 1.0f / (float)p.PC; p.inv_tiles_w = 1.0f / (float)tiles_w;
+        p.mg_TW = division_constant(TW); p.mg_Hp = division_constant(Hp); p.mg_Ho = division_constant(a.Ho);
+        p.mg_PC = division_constant(p.PC); p.mg_tiles_w = division_constant(tiles_w);
         p.step_q = (256 / UPP) / p.PC;
         p.step_r = (256 / UPP) % p.PC;
         // a layer whose wave groups each see a single stage never touches the second
@@ -721,7 +730,7 @@ bool plan_patch(const DsqConvArgs &a, int BP, int BC, int PF, int CT, int UPT, i
         if (plan_lds_bytes(p, BC) > lds_limit) continue;
         if (p.units > 256 * UPT) continue;
         const long long tiles = (long long)p.tiles_w * p.row_tiles;
-        // index divisions in the kernel use float reciprocals: keep operands small
+        // keep the operands of the index arithmetic small
         if (tiles * ((a.C_out + BC - 1) / BC) >= (1 << 22) || (long long)a.N * Hp >= (1 << 22) || NHo >= (1 << 22)) continue;
         // equal work: prefer a footprint that lets three (else two) workgroups share a CU,
         // then the smaller patch
@@ -745,7 +754,7 @@ hipError_t launch_kernel(const DsqConvArgs &a, const PatchPlan &pl, hipStream_t 
     }
     PatchPlan p2 = pl;
     p2.tiles_c = (a.C_out + BC - 1) / BC;
-    p2.inv_tiles_c = 1.0f / (float)p2.tiles_c;
+    p2.mg_tiles_c = division_constant(p2.tiles_c);
     p2.total_blocks = pl.tiles_w * pl.row_tiles * p2.tiles_c;
     p2.xcd_chunk = (p2.total_blocks + 7) / 8;
     kern<<<dim3(8 * p2.xcd_chunk), 256 * KS, lds, stream>>>(a, p2);

@@ -14,6 +14,7 @@ struct DsqConvArgs {
     const void *act;          // packed activation codes
     const int32_t *pix_sum;   // [N*H*W]
     float l_a, u_a;
+    float delta_a;            // (u_a - l_a) / (2^bits - 1) in binary32, computed by the host
     const void *wq;           // packed weights
     const float *delta_w;     // [Cop]
     const float *l_w;         // [Cop]
