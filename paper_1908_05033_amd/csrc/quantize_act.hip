@@ -58,21 +58,22 @@ template <bool VEC, int MODE>
 __device__ __forceinline__ uint32_t quant4(const float *px, int c0, int C, const QuantParams &qp,
                                            const float2 *tp)
 {
-    float v0 = 0.f, v1 = 0.f, v2 = 0.f, v3 = 0.f;
-    bool in0, in1, in2, in3;
     if (VEC) {
-        in0 = in1 = in2 = in3 = c0 < C;
-        if (in0) {
-            float4 f = *reinterpret_cast<const float4 *>(px + c0);
-            v0 = f.x; v1 = f.y; v2 = f.z; v3 = f.w;
-        }
-    } else {
-        in0 = c0 < C; in1 = c0 + 1 < C; in2 = c0 + 2 < C; in3 = c0 + 3 < C;
-        if (in0) v0 = px[c0];
-        if (in1) v1 = px[c0 + 1];
-        if (in2) v2 = px[c0 + 2];
-        if (in3) v3 = px[c0 + 3];
+        // C is a multiple of 4 here.  Branch-free: a group past the last channel
+        // reads the pixel's first four values instead and is blanked afterwards,
+        // so that all loads of a thread are in flight together.
+        const bool in = c0 < C;
+        const float4 f = *reinterpret_cast<const float4 *>(px + (in ? c0 : 0));
+        const uint32_t b = dsq_bytes4(qcode<MODE>(f.x, qp, tp), qcode<MODE>(f.y, qp, tp),
+                                      qcode<MODE>(f.z, qp, tp), qcode<MODE>(f.w, qp, tp));
+        return in ? b : 0u;
     }
+    const bool in0 = c0 < C, in1 = c0 + 1 < C, in2 = c0 + 2 < C, in3 = c0 + 3 < C;
+    float v0 = 0.f, v1 = 0.f, v2 = 0.f, v3 = 0.f;
+    if (in0) v0 = px[c0];
+    if (in1) v1 = px[c0 + 1];
+    if (in2) v2 = px[c0 + 2];
+    if (in3) v3 = px[c0 + 3];
     const int q0 = in0 ? qcode<MODE>(v0, qp, tp) : 0;
     const int q1 = in1 ? qcode<MODE>(v1, qp, tp) : 0;
     const int q2 = in2 ? qcode<MODE>(v2, qp, tp) : 0;
