@@ -800,7 +800,10 @@ int pick_tile(const DsqConvArgs &a)
     // of its channels; the 256x64 tile when it still runs in two rounds or more;
     // otherwise the 128x64 tile
     const int c_pad = ((a.C_out + 127) / 128) * 128;
-    if (a.C_out > 64 && 4 * (c_pad - a.C_out) <= c_pad && blocks(kMedium) >= (a.R == 1 ? 320 : 192)) {
+    // (a 1x1 layer with at most 64 input channels is one matrix instruction deep:
+    // wasted channels cost nothing there, fewer and wider output tiles still pay)
+    const int waste_limit = (a.R == 1 && a.Cp <= 64) ? 2 : 4;
+    if (a.C_out > 64 && waste_limit * (c_pad - a.C_out) <= c_pad && blocks(kMedium) >= (a.R == 1 ? 320 : 192)) {
         // 2-bit layers (FP4 path: the 256x128 tile fits its registers): take that
         // tile when the 128x128 one leaves a nearly empty last round of workgroups
         // (3 per CU, 768 at a time) and the large one (2 per CU, 512) does not
