@@ -60,10 +60,13 @@ float dsq_oracle_delta(float l, float u, int bits)
  * A value exactly half way between two points goes to the upper one: that is
  * what step 3 (sgn of phi, with sgn(0) = +1 from the binary quantizer of
  * Sec. 3.1) yields at x = m_i.  Every operation is binary32, the division is
- * a true division.  NaN clips to l (fmaxf returns its non-NaN operand). */
+ * a true division.  A NaN of either kind clips to l: the clip is written as two
+ * comparisons (a NaN compares false), not as fmaxf/fminf, whose result for a
+ * signalling NaN depends on the C library. */
 static int code_of(float x, float l, float u, float delta, int top)
 {
-    float v = fminf(fmaxf(x, l), u);
+    float v = x > l ? x : l;
+    v = v < u ? v : u;
     float t = (v - l) / delta;
     float r = floorf(t + 0.5f);
     int c = (int)r;

@@ -130,6 +130,14 @@ def test_special_values_and_bad_bounds():
     code = oracle.quantize(x, -1.0, 1.0, 4)
     assert code.tolist()[:3] == [0, 15, 0]
     assert code[3] == code[4]             # -0.0 and +0.0 are the same number
+    # every NaN, quiet or signalling, of either sign, clips to l (code 0) whatever the range
+    nans = np.array([0x7F800001, 0x7FBFFFFF, 0x7FC00000, 0x7FFFFFFF, 0xFF800001, 0xFFC00000, 0xFFFFFFFF],
+                    np.uint32).view(np.float32)
+    for bits in (1, 2, 3, 4):
+        assert not oracle.quantize(nans, -1.0, 1.0, bits).any()
+        assert not oracle.quantize(nans, 0.25, 2.0, bits).any()
+    w = np.tile(nans, 2).reshape(2, 7, 1, 1)
+    assert not oracle.quantize_weights(w, np.array([-1.0, 0.5], np.float32), np.array([1.0, 0.75], np.float32), 3).any()
     z = oracle.quantize(np.array([0.0, -0.0], np.float32), -1.5, 1.5, 2)
     assert z.tolist() == [2, 2]           # Delta = 1 exactly: t = 1.5 -> tie -> up
     for l, u in [(1.0, 1.0), (2.0, 1.0), (float("nan"), 1.0), (0.0, float("inf"))]:
