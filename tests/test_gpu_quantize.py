@@ -124,3 +124,61 @@ def test_weight_codes_at_cfg2_size():
     got, aux = _pack_gpu(inp["w"], inp["l_w"], inp["u_w"], 4)
     want = oracle.quantize_weights(inp["w"].numpy(), inp["l_w"], inp["u_w"], 4)
     assert np.array_equal(got[:256, :256], want)
+
+
+def _pack_reference(oc, bits):
+    """Oracle codes [P, 64] (uint8, on the GPU) -> the packed bytes the header
+    documents: 4-bit containers, byte j of word w = c[8w+j] | c[8w+4+j] << 4;
+    2-bit containers, byte j = c[16w+j] | c[16w+4+j] << 2 | c[16w+8+j] << 4 | c[16w+12+j] << 6."""
+    P = oc.shape[0]
+    if container(bits) == 4:
+        g = oc.reshape(P, 8, 2, 4)
+        return (g[:, :, 0, :] | (g[:, :, 1, :] << 4)).reshape(P, 32)
+    g = oc.reshape(P, 4, 4, 4)
+    return (g[:, :, 0, :] | (g[:, :, 1, :] << 2) | (g[:, :, 2, :] << 4) | (g[:, :, 3, :] << 6)).reshape(P, 16)
+
+
+@pytest.mark.parametrize("layout", [B.DSQ_NHWC, B.DSQ_NCHW])
+@pytest.mark.parametrize("bits,l,u", [(4, 0.0, 2.3217), (2, -0.7301, 1.9102), (3, 0.0, 6.0), (1, -1.0, 1.0)])
+def test_every_float_bit_pattern_gets_the_oracle_code(bits, l, u, layout):
+    """All 2^32 binary32 patterns (NaNs of both kinds, infinities, denormals) against
+    the oracle's division recipe, packed codes and pixel sums bit for bit: through
+    the large-tensor NHWC kernel, whose quantizer is the step-function form, and
+    through the NCHW kernel, which evaluates the recipe itself on the device."""
+    from concurrent.futures import ThreadPoolExecutor
+    l, u = float(np.float32(l)), float(np.float32(u))
+    CH = 1 << 27                                 # patterns per launch: 2^21 pixels of 64 channels
+    P, C = CH // 64, 64
+    N, H, W = 1, P // 1024, 1024
+    codes = torch.empty((B.dsq_act_packed_bytes(N, H, W, C, bits),), dtype=torch.uint8, device="cuda")
+    pix = torch.empty((P,), dtype=torch.int32, device="cuda")
+    workers = 8
+    sub = CH // workers
+
+    def oracle_part(args):
+        start, k = args
+        bits32 = (np.arange(start + k * sub, start + (k + 1) * sub, dtype=np.uint64) & 0xFFFFFFFF).astype(np.uint32)
+        return oracle.quantize(bits32.view(np.float32), l, u, bits)
+
+    with ThreadPoolExecutor(workers) as pool:
+        for start in range(0, 1 << 32, CH):
+            idx = torch.arange(start, start + CH, dtype=torch.int64, device="cuda")
+            idx = torch.where(idx >= (1 << 31), idx - (1 << 32), idx).to(torch.int32)
+            x = idx.view(torch.float32)
+            del idx
+            B.dsq_quantize_act(x, layout, N, C, H, W, l, u, bits, codes, pix)
+            want = np.concatenate(list(pool.map(oracle_part, [(start, k) for k in range(workers)])))
+            oc = torch.from_numpy(want).cuda()
+            # NHWC: pattern k is channel k % 64 of pixel k / 64; NCHW: pixel k % P of channel k / P
+            oc = oc.reshape(P, 64) if layout == B.DSQ_NHWC else oc.reshape(64, P).t().contiguous()
+            torch.cuda.synchronize()
+            ref = _pack_reference(oc, bits)
+            same = torch.equal(codes.reshape(P, -1), ref)
+            sums_same = torch.equal(pix, oc.sum(dim=1, dtype=torch.int32))
+            if not (same and sums_same):
+                bad = (codes.reshape(P, -1) != ref).nonzero()
+                where = int(bad[0, 0]) if len(bad) else -1
+                raise AssertionError("bits=%d range=(%r, %r): mismatch in the chunk of patterns starting at 0x%08x "
+                                     "(first differing pixel %d, codes equal: %s, sums equal: %s)"
+                                     % (bits, l, u, start, where, same, sums_same))
+            del x, oc, ref
