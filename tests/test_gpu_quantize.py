@@ -119,6 +119,35 @@ def test_weight_codes_layout_and_side_tables(shape, bits):
     assert np.array_equal(aux2["sw_tap"], aux["sw_tap"])
 
 
+@pytest.mark.parametrize("bits", [1, 2, 3, 4])
+def test_weight_codes_of_special_values(bits):
+    """NaNs of both kinds, infinities, zeros of both signs, denormals and every
+    float within a few ulps of each threshold as weights."""
+    L = 2 ** bits - 1
+    lw = np.array([-0.0719, 0.0, -1.0], np.float32)
+    uw = np.array([0.0931, 0.5 * L, 1.0], np.float32)
+    special = np.array([0x7F800001, 0x7FBFFFFF, 0x7FC00000, 0xFFC00001, 0xFF800001, 0x7F800000, 0xFF800000,
+                        0x00000000, 0x80000000, 0x00000001, 0x80000001, 0x7F7FFFFF, 0xFF7FFFFF], np.uint32)
+    rows = []
+    for l, u in zip(lw, uw):
+        d = (np.float32(u) - np.float32(l)) / np.float32(L)
+        vals = list(special.view(np.float32))
+        for j in range(L + 1):
+            t = np.float32(np.float32(l) + np.float32(j + 0.5) * d)
+            lo = hi = t
+            vals.append(t)
+            for _ in range(5):
+                lo = np.nextafter(lo, np.float32(-np.inf), dtype=np.float32)
+                hi = np.nextafter(hi, np.float32(np.inf), dtype=np.float32)
+                vals += [lo, hi]
+        rows.append(np.array(vals, np.float32))
+    w = torch.from_numpy(np.stack(rows).reshape(3, -1, 1, 1).copy())
+    got, aux = _pack_gpu(w, lw, uw, bits)
+    want = oracle.quantize_weights(w.numpy(), lw, uw, bits)
+    assert np.array_equal(got[:3, :w.shape[1]], want)
+    assert np.array_equal(aux["sw_total"][:3], want.astype(np.int64).sum(axis=(1, 2, 3)))
+
+
 def test_weight_codes_at_cfg2_size():
     layer, inp = inputs.make_config_layer(2)
     got, aux = _pack_gpu(inp["w"], inp["l_w"], inp["u_w"], 4)
