@@ -132,3 +132,15 @@ def assert_out_close(gpu, ref, delta_a, delta_w, rel=1e-5):
     assert not bad.any(), "%d elements off, worst %.3e (ref %.3e)" % (
         bad.sum(), err.max(), np.abs(r).max())
     assert err.max() <= rel * np.abs(r).max() + floor.max()
+
+
+def pack_codes_reference(oc, bits):
+    """Codes [P, 64] (uint8 torch tensor) -> the packed bytes the header
+    documents: 4-bit containers, byte j of word w = c[8w+j] | c[8w+4+j] << 4;
+    2-bit containers, byte j = c[16w+j] | c[16w+4+j] << 2 | c[16w+8+j] << 4 | c[16w+12+j] << 6."""
+    P = oc.shape[0]
+    if container(bits) == 4:
+        g = oc.reshape(P, 8, 2, 4)
+        return (g[:, :, 0, :] | (g[:, :, 1, :] << 4)).reshape(P, 32)
+    g = oc.reshape(P, 4, 4, 4)
+    return (g[:, :, 0, :] | (g[:, :, 1, :] << 2) | (g[:, :, 2, :] << 4) | (g[:, :, 3, :] << 6)).reshape(P, 16)

@@ -5,7 +5,7 @@ import pytest
 import torch
 
 import oracle
-from helpers import container, round_up, split_aux, unpack_act, unpack_weights
+from helpers import container, pack_codes_reference, round_up, split_aux, unpack_act, unpack_weights
 from paper_1908_05033_amd import binding as B
 from paper_1908_05033_amd import inputs
 
@@ -155,18 +155,6 @@ def test_weight_codes_at_cfg2_size():
     assert np.array_equal(got[:256, :256], want)
 
 
-def _pack_reference(oc, bits):
-    """Oracle codes [P, 64] (uint8, on the GPU) -> the packed bytes the header
-    documents: 4-bit containers, byte j of word w = c[8w+j] | c[8w+4+j] << 4;
-    2-bit containers, byte j = c[16w+j] | c[16w+4+j] << 2 | c[16w+8+j] << 4 | c[16w+12+j] << 6."""
-    P = oc.shape[0]
-    if container(bits) == 4:
-        g = oc.reshape(P, 8, 2, 4)
-        return (g[:, :, 0, :] | (g[:, :, 1, :] << 4)).reshape(P, 32)
-    g = oc.reshape(P, 4, 4, 4)
-    return (g[:, :, 0, :] | (g[:, :, 1, :] << 2) | (g[:, :, 2, :] << 4) | (g[:, :, 3, :] << 6)).reshape(P, 16)
-
-
 @pytest.mark.parametrize("layout", [B.DSQ_NHWC, B.DSQ_NCHW])
 @pytest.mark.parametrize("bits,l,u", [(4, 0.0, 2.3217), (2, -0.7301, 1.9102), (3, 0.0, 6.0), (1, -1.0, 1.0)])
 def test_every_float_bit_pattern_gets_the_oracle_code(bits, l, u, layout):
@@ -201,7 +189,7 @@ def test_every_float_bit_pattern_gets_the_oracle_code(bits, l, u, layout):
             # NHWC: pattern k is channel k % 64 of pixel k / 64; NCHW: pixel k % P of channel k / P
             oc = oc.reshape(P, 64) if layout == B.DSQ_NHWC else oc.reshape(64, P).t().contiguous()
             torch.cuda.synchronize()
-            ref = _pack_reference(oc, bits)
+            ref = pack_codes_reference(oc, bits)
             same = torch.equal(codes.reshape(P, -1), ref)
             sums_same = torch.equal(pix, oc.sum(dim=1, dtype=torch.int32))
             if not (same and sums_same):

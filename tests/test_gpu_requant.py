@@ -14,7 +14,7 @@ import pytest
 import torch
 
 import oracle
-from helpers import oracle_layer, round_up, unpack_act
+from helpers import oracle_layer, pack_codes_reference, round_up, unpack_act
 from paper_1908_05033_amd import binding as B
 from paper_1908_05033_amd import inputs
 
@@ -259,3 +259,65 @@ def test_every_float_around_every_quantizer_threshold(l_n, u_n, bits_n, kernel):
     want = oracle.quantize(shift, l_n, u_n, bits_n)            # (NaN -> code 0 by the recipe)
     got, pix, *_ = run_requant_gpu(layer, inp, scale, shift, False, l_n, u_n, bits_n, kernel)
     assert np.array_equal(got[..., :C_out], np.broadcast_to(want, got[..., :C_out].shape))
+
+
+@pytest.mark.parametrize("kernel", [0, 1])
+@pytest.mark.parametrize("relu", [False, True])
+@pytest.mark.parametrize("l_n,u_n,bits_n", [(0.0, 2.45, 4), (-0.35, 1.3, 2)])
+def test_every_float_bit_pattern_through_the_chained_quantizer(l_n, u_n, bits_n, relu, kernel):
+    """All 2^32 binary32 patterns as the value z that reaches the next layer's
+    quantizer (zero weights make the layer output +0, so z = 0 * scale + shift[o]
+    = shift[o]), 2^20 output channels per launch, against the oracle: the tuned
+    kernel's step-function form and the simple kernel's division, with and
+    without the ReLU, packed codes and pixel sums bit for bit."""
+    from concurrent.futures import ThreadPoolExecutor
+    l_n, u_n = float(np.float32(l_n)), float(np.float32(u_n))
+    CO = 1 << 20                                  # output channels (= patterns) per launch
+    GROUP = 128                                   # launches per comparison
+    buf = B.alloc_layer(1, 64, 1, 1, CO, 1, 1, 1, 0, 4)
+    x = torch.zeros((1, 1, 1, 64), device="cuda")
+    B.dsq_quantize_act(x, B.DSQ_NHWC, 1, 64, 1, 1, 0.0, 2.0, 4, buf.act_packed, buf.pix_code_sum)
+    zeros_w = torch.zeros((CO, 64, 1, 1), device="cuda")
+    B.dsq_pack_weights(zeros_w, torch.zeros(CO, device="cuda"), torch.ones(CO, device="cuda"), None,
+                       CO, 64, 1, 1, 4, buf.w_packed, buf.w_aux)
+    del zeros_w
+    scale = torch.full((CO,), 1.5, device="cuda")
+    per_launch = B.dsq_act_packed_bytes(1, 1, 1, CO, bits_n)
+    codes = torch.empty((GROUP, per_launch), dtype=torch.uint8, device="cuda")
+    pix = torch.empty((GROUP, 4), dtype=torch.int32, device="cuda")          # (16-byte aligned rows)
+    workers = 8
+    n = GROUP * CO
+    sub = n // workers
+
+    def oracle_part(args):
+        start, k = args
+        b32 = (np.arange(start + k * sub, start + (k + 1) * sub, dtype=np.uint64) & 0xFFFFFFFF).astype(np.uint32)
+        y = np.zeros((1, sub, 1, 1), np.float32)
+        return oracle.requantize(y, np.full(sub, 1.5, np.float32), b32.view(np.float32), relu, l_n, u_n, bits_n)
+
+    prev = B.dsq_set_conv_kernel(kernel)
+    try:
+        with ThreadPoolExecutor(workers) as pool:
+            for start in range(0, 1 << 32, n):
+                idx = torch.arange(start, start + n, dtype=torch.int64, device="cuda")
+                shift = torch.where(idx >= (1 << 31), idx - (1 << 32), idx).to(torch.int32).view(torch.float32)
+                del idx
+                for k in range(GROUP):
+                    B.dsq_conv2d_requant(buf.desc, buf.act_packed, buf.pix_code_sum, 0.0, 2.0, buf.w_packed,
+                                         buf.w_aux, scale, shift[k * CO:(k + 1) * CO], relu, l_n, u_n, bits_n,
+                                         codes[k], pix[k])
+                want = np.concatenate(list(pool.map(oracle_part, [(start, k) for k in range(workers)])))
+                oc = torch.from_numpy(want.reshape(-1)).cuda().reshape(GROUP, CO)
+                torch.cuda.synchronize()
+                ref = pack_codes_reference(oc.reshape(-1, 64), bits_n).reshape(GROUP, per_launch)
+                same = torch.equal(codes, ref)
+                sums_same = torch.equal(pix[:, 0], oc.sum(dim=1, dtype=torch.int32))
+                if not (same and sums_same):
+                    bad = (codes != ref).nonzero()
+                    raise AssertionError("range (%r, %r) bits %d relu %s kernel %d: mismatch in the patterns from 0x%08x "
+                                         "(first differing launch/byte %s; codes equal %s, sums equal %s)"
+                                         % (l_n, u_n, bits_n, relu, kernel, start,
+                                            bad[0].tolist() if len(bad) else None, same, sums_same))
+                del shift, oc, ref
+    finally:
+        B.dsq_set_conv_kernel(prev)
