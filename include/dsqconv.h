@@ -81,7 +81,9 @@ typedef enum {
     DSQ_OK = 0,
     DSQ_ERR_NULL = 1,        /* a required pointer is NULL */
     DSQ_ERR_BITS = 2,        /* bits not in {1,2,3,4} */
-    DSQ_ERR_RANGE = 3,       /* !(l < u) or a bound is not finite */
+    DSQ_ERR_RANGE = 3,       /* !(l < u), a bound is not finite, or the width
+                                u - l of an activation range is outside
+                                [1e-30, 1e30] */
     DSQ_ERR_SHAPE = 4,       /* a dimension <= 0, or Ho/Wo <= 0 */
     DSQ_ERR_UNSUPPORTED = 5, /* R != S, R not in {1,3}, stride not in {1,2},
                                 pad > R-1, a tensor of 2^31 or more elements,

@@ -13,7 +13,15 @@ int g_conv_kernel = 0;   // 0 auto, 1 simple, 2 patch (auto tile), 3..6 patch wi
 
 bool bits_ok(int bits) { return bits >= 1 && bits <= 4; }
 bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
-bool range_ok(float l, float u) { return isfinite(l) && isfinite(u) && l < u; }
+// A clip range must be finite, ordered, and of a width whose step Delta = (u - l) / (2^b - 1)
+// and the reciprocal of it are normal binary32 numbers with room to spare: the
+// step-function kernels start from the guess (v - l) * (1 / Delta).
+bool range_ok(float l, float u)
+{
+    if (!(isfinite(l) && isfinite(u) && l < u)) return false;
+    const float width = u - l;
+    return width >= 1e-30f && width <= 1e30f;
+}
 const long long kMaxElems = (1LL << 31) - 1;
 
 void quantizer_thresholds(float l, float u, int bits, float thr[16]);

@@ -64,6 +64,7 @@ def test_quantize_act_rejects_bad_arguments():
     assert _q(bits=0) == 2 and _q(bits=5) == 2
     assert _q(l=1.0, u=1.0) == 3 and _q(l=2.0, u=1.0) == 3
     assert _q(l=float("nan")) == 3 and _q(u=float("inf")) == 3
+    assert _q(l=0.0, u=1e-38) == 3 and _q(l=-3e38, u=3e38) == 3 and _q(l=0.0, u=9e-31) == 3
     assert _q(N=0) == 4 and _q(Cc=-1) == 4
     assert _q(layout=7) == 5
     assert _q(N=1 << 15, H=1 << 8, W=1 << 8, Cc=64, nbytes=1 << 62) == 5
@@ -99,7 +100,7 @@ def test_conv2d_rejects_bad_arguments():
     assert lib.dsq_conv2d(None, FAKE, FAKE, 0.0, 1.0, FAKE, FAKE, FAKE, 0, None, None) == 1
     assert _c(act=None) == 1 and _c(out=None) == 1 and _c(aux=None) == 1
     assert _c(bits=7) == 2
-    assert _c(la=1.0, ua=0.0) == 3
+    assert _c(la=1.0, ua=0.0) == 3 and _c(la=0.0, ua=1e-37) == 3 and _c(la=-2e38, ua=2e38) == 3
     assert _c(N=0) == 4 and _c(H=1, W=1, pad=0) == 4
     assert _c(R=3, S=1) == 5 and _c(R=5, S=5, pad=2) == 5
     assert _c(stride=3) == 5 and _c(pad=3) == 5 and _c(R=1, S=1, pad=1) == 5
@@ -135,6 +136,7 @@ def test_conv2d_requant_rejects_bad_arguments():
     assert _r(codes=None) == 1 and _r(pixn=None) == 1 and _r(act=None) == 1
     assert _r(bn=0) == 2 and _r(bn=5) == 2 and _r(bits=9) == 2
     assert _r(ln=1.0, un=1.0) == 3 and _r(un=float("inf")) == 3 and _r(la=2.0, ua=1.0) == 3
+    assert _r(ln=0.0, un=1e-36) == 3 and _r(ln=-3e38, un=3e38) == 3
     assert _r(C_out=0) == 4
     assert _r(stride=4) == 5
     assert _r(codes=FAKE + 8) == 6 and _r(scale=FAKE + 4) == 6 and _r(shift=FAKE + 12) == 6
