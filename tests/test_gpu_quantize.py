@@ -156,7 +156,8 @@ def test_weight_codes_at_cfg2_size():
 
 
 @pytest.mark.parametrize("layout", [B.DSQ_NHWC, B.DSQ_NCHW])
-@pytest.mark.parametrize("bits,l,u", [(4, 0.0, 2.3217), (2, -0.7301, 1.9102), (3, 0.0, 6.0), (1, -1.0, 1.0)])
+@pytest.mark.parametrize("bits,l,u", [(4, 0.0, 2.3217), (2, -0.7301, 1.9102), (3, 0.0, 6.0), (1, -1.0, 1.0),
+                                      (4, 0.0, 1.5e-30), (4, -4e29, 5e29), (4, 1000.0, 1000.5)])
 def test_every_float_bit_pattern_gets_the_oracle_code(bits, l, u, layout):
     """All 2^32 binary32 patterns (NaNs of both kinds, infinities, denormals) against
     the oracle's division recipe, packed codes and pixel sums bit for bit: through
