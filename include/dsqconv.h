@@ -25,10 +25,8 @@
  *     error nothing has been enqueued.  Errors are return codes only.
  *   - Device pointers must be 16-byte aligned.
  *   - bits is 1, 2, 3 or 4.  The descriptor's bits is the activations' width; the
- *     weights may have been packed with another width of the same container
- *     class ({1,2} or {3,4}, e.g. 3-bit weights under 4-bit activations): their
- *     step travels in w_aux.  Widths of different container classes in one
- *     layer are not supported.
+ *     weights may have another one (dsq_pack_weights_for; their step travels in
+ *     w_aux), except 3- or 4-bit weights under 1- or 2-bit activations.
  *     bits = 1 is the binary case of Sec. 3.1: with (l, u) = (-1, +1) the two
  *     levels are sgn(x) (code 1 for x >= 0), and any other (l, u) gives the
  *     two-level quantizer with levels l and u.
@@ -145,6 +143,23 @@ dsq_status dsq_pack_weights(const float *w_oihw, const float *l_w,
                             int C_out, int C_in, int R, int S, int bits,
                             void *w_packed, size_t w_bytes, void *w_aux,
                             size_t aux_bytes, void *hip_stream);
+
+/* ---- dsq_pack_weights_for: weights and activations of different widths ---
+ * Sec. 3.1 gives every quantizer its own b.  The same as dsq_pack_weights,
+ * for a layer whose activations have bits_act bits (the descriptor's bits,
+ * the width given to dsq_quantize_act) while the weights have bits_w: the
+ * weight codes are stored in the fields of that layer's container, so any
+ * bits_w goes with 3- or 4-bit activations and 1- or 2-bit weights go with
+ * 1- or 2-bit activations; 3- or 4-bit weights under 1- or 2-bit activations
+ * give DSQ_ERR_UNSUPPORTED.  dsq_pack_weights(.., bits, ..) is the case
+ * bits_w = bits_act = bits.
+ */
+dsq_status dsq_pack_weights_for(const float *w_oihw, const float *l_w,
+                                const float *u_w, const uint8_t *codes_oihw,
+                                int C_out, int C_in, int R, int S, int bits_w,
+                                int bits_act, void *w_packed, size_t w_bytes,
+                                void *w_aux, size_t aux_bytes,
+                                void *hip_stream);
 
 /* ---- dsq_conv2d: Alg. 1 steps 4 and 5 ----------------------------------
  * Computes, for every output pixel m = (n, oy, ox) and output channel o,

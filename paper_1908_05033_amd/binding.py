@@ -20,7 +20,7 @@ DSQ_OK = 0
 
 EXPORTS = [
     "dsq_act_packed_bytes", "dsq_wgt_packed_bytes", "dsq_wgt_aux_bytes",
-    "dsq_quantize_act", "dsq_pack_weights", "dsq_conv2d", "dsq_conv2d_requant",
+    "dsq_quantize_act", "dsq_pack_weights", "dsq_pack_weights_for", "dsq_conv2d", "dsq_conv2d_requant",
     "dsq_soft_quantize_fwd", "dsq_soft_quantize_bwd",
     "dsq_set_conv_kernel", "dsq_status_string",
 ]
@@ -62,6 +62,8 @@ def load_library():
     lib.dsq_quantize_act.argtypes = [vp, i, i, i, i, i, f, f, i, vp, sz, vp, vp]
     lib.dsq_pack_weights.restype = i
     lib.dsq_pack_weights.argtypes = [vp, vp, vp, vp, i, i, i, i, i, vp, sz, vp, sz, vp]
+    lib.dsq_pack_weights_for.restype = i
+    lib.dsq_pack_weights_for.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, vp, sz, vp, sz, vp]
     lib.dsq_conv2d.restype = i
     lib.dsq_conv2d.argtypes = [C.POINTER(dsq_conv_desc), vp, vp, f, f, vp, vp, vp, i, vp, vp]
     lib.dsq_conv2d_requant.restype = i
@@ -133,6 +135,17 @@ def dsq_pack_weights(w_oihw, l_w, u_w, codes_oihw, C_out, C_in, R, S, bits, w_pa
         _dev_ptr(w_oihw, torch.float32, True), _dev_ptr(l_w, torch.float32),
         _dev_ptr(u_w, torch.float32), _dev_ptr(codes_oihw, torch.uint8, True),
         C_out, C_in, R, S, bits,
+        _dev_ptr(w_packed, torch.uint8), w_packed.numel() if w_packed is not None else 0,
+        _dev_ptr(w_aux, torch.uint8), w_aux.numel() if w_aux is not None else 0,
+        _stream(stream)))
+
+
+def dsq_pack_weights_for(w_oihw, l_w, u_w, codes_oihw, C_out, C_in, R, S, bits_w, bits_act, w_packed, w_aux,
+                         stream=None):
+    _check(load_library().dsq_pack_weights_for(
+        _dev_ptr(w_oihw, torch.float32, True), _dev_ptr(l_w, torch.float32),
+        _dev_ptr(u_w, torch.float32), _dev_ptr(codes_oihw, torch.uint8, True),
+        C_out, C_in, R, S, bits_w, bits_act,
         _dev_ptr(w_packed, torch.uint8), w_packed.numel() if w_packed is not None else 0,
         _dev_ptr(w_aux, torch.uint8), w_aux.numel() if w_aux is not None else 0,
         _stream(stream)))

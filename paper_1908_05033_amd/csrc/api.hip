@@ -70,23 +70,35 @@ dsq_status dsq_quantize_act(const float *x, dsq_layout layout, int N, int C, int
     return e == hipSuccess ? DSQ_OK : DSQ_ERR_HIP;
 }
 
+dsq_status dsq_pack_weights_for(const float *w_oihw, const float *l_w, const float *u_w,
+                                const uint8_t *codes_oihw, int C_out, int C_in, int R, int S,
+                                int bits_w, int bits_act, void *w_packed, size_t w_bytes, void *w_aux,
+                                size_t aux_bytes, void *hip_stream)
+{
+    if ((!w_oihw && !codes_oihw) || !l_w || !u_w || !w_packed || !w_aux) return DSQ_ERR_NULL;
+    if (!bits_ok(bits_w) || !bits_ok(bits_act)) return DSQ_ERR_BITS;
+    if (C_out <= 0 || C_in <= 0 || R <= 0 || S <= 0) return DSQ_ERR_SHAPE;
+    if (R != S || (R != 1 && R != 3)) return DSQ_ERR_UNSUPPORTED;
+    // 3/4-bit weight codes do not fit the fields of a layer with 1/2-bit activations
+    if (dsq_container(bits_w) > dsq_container(bits_act)) return DSQ_ERR_UNSUPPORTED;
+    if ((long long)dsq_round_up(C_out, 256) * dsq_round_up(C_in, 64) * R * S > kMaxElems)
+        return DSQ_ERR_UNSUPPORTED;
+    if (!aligned16(w_packed) || !aligned16(w_aux)) return DSQ_ERR_ALIGN;
+    if (w_bytes < dsq_wgt_packed_bytes(C_out, C_in, R, S, bits_act)) return DSQ_ERR_SIZE;
+    if (aux_bytes < dsq_wgt_aux_bytes(C_out, R, S)) return DSQ_ERR_SIZE;
+    hipError_t e = dsq_launch_pack_weights(w_oihw, l_w, u_w, codes_oihw, C_out, C_in, R, bits_w,
+                                           dsq_container(bits_act), w_packed, w_aux,
+                                           (hipStream_t)hip_stream);
+    return e == hipSuccess ? DSQ_OK : DSQ_ERR_HIP;
+}
+
 dsq_status dsq_pack_weights(const float *w_oihw, const float *l_w, const float *u_w,
                             const uint8_t *codes_oihw, int C_out, int C_in, int R, int S, int bits,
                             void *w_packed, size_t w_bytes, void *w_aux, size_t aux_bytes,
                             void *hip_stream)
 {
-    if ((!w_oihw && !codes_oihw) || !l_w || !u_w || !w_packed || !w_aux) return DSQ_ERR_NULL;
-    if (!bits_ok(bits)) return DSQ_ERR_BITS;
-    if (C_out <= 0 || C_in <= 0 || R <= 0 || S <= 0) return DSQ_ERR_SHAPE;
-    if (R != S || (R != 1 && R != 3)) return DSQ_ERR_UNSUPPORTED;
-    if ((long long)dsq_round_up(C_out, 256) * dsq_round_up(C_in, 64) * R * S > kMaxElems)
-        return DSQ_ERR_UNSUPPORTED;
-    if (!aligned16(w_packed) || !aligned16(w_aux)) return DSQ_ERR_ALIGN;
-    if (w_bytes < dsq_wgt_packed_bytes(C_out, C_in, R, S, bits)) return DSQ_ERR_SIZE;
-    if (aux_bytes < dsq_wgt_aux_bytes(C_out, R, S)) return DSQ_ERR_SIZE;
-    hipError_t e = dsq_launch_pack_weights(w_oihw, l_w, u_w, codes_oihw, C_out, C_in, R, bits,
-                                           w_packed, w_aux, (hipStream_t)hip_stream);
-    return e == hipSuccess ? DSQ_OK : DSQ_ERR_HIP;
+    return dsq_pack_weights_for(w_oihw, l_w, u_w, codes_oihw, C_out, C_in, R, S, bits, bits, w_packed,
+                                w_bytes, w_aux, aux_bytes, hip_stream);
 }
 
 namespace {

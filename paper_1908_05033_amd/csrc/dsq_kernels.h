@@ -57,8 +57,10 @@ hipError_t dsq_launch_quantize_act(const float *x, int layout_nchw, int N, int C
                                    float l, float u, int bits, const DsqThresholds &th, void *codes,
                                    int32_t *pix_sum, hipStream_t stream);
 
+// `cont`: the container (2 or 4 bits) of the layer the weights are for; codes of
+// `bits` <= cont bits are stored in it.
 hipError_t dsq_launch_pack_weights(const float *w, const float *l_w, const float *u_w,
-                                   const uint8_t *codes, int C_out, int C_in, int R, int bits,
+                                   const uint8_t *codes, int C_out, int C_in, int R, int bits, int cont,
                                    void *w_packed, void *w_aux, hipStream_t stream);
 
 // Constants of the training-mode DSQ function for one tensor, computed on the

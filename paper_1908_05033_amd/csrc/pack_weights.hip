@@ -110,10 +110,9 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(
 }  // namespace
 
 hipError_t dsq_launch_pack_weights(const float *w, const float *l_w, const float *u_w,
-                                   const uint8_t *codes, int C_out, int C_in, int R, int bits,
+                                   const uint8_t *codes, int C_out, int C_in, int R, int bits, int cont,
                                    void *w_packed, void *w_aux, hipStream_t stream)
 {
-    const int cont = dsq_container(bits);
     const int top = (1 << bits) - 1;
     const int T = R * R;
     const int Cop = dsq_round_up(C_out, 256);

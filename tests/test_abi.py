@@ -87,6 +87,16 @@ def test_pack_weights_rejects_bad_arguments():
     assert _p(wb=100) == 7 and _p(ab=100) == 7
 
 
+def test_pack_weights_for_rejects_bad_arguments():
+    lib = B.load_library()
+    f = lambda bw=2, ba=4, w=FAKE, wb=1 << 24: lib.dsq_pack_weights_for(w, FAKE, FAKE, None, 8, 8, 3, 3, bw, ba, FAKE, wb,
+                                                                        FAKE, 1 << 20, None)
+    assert f(bw=0) == 2 and f(ba=5) == 2
+    assert f(bw=4, ba=2) == 5 and f(bw=3, ba=1) == 5          # wide weight codes, narrow fields
+    assert f(w=None) == 1
+    assert f(wb=100) == 7
+
+
 def _c(desc=None, act=FAKE, pix=FAKE, la=0.0, ua=1.0, wp=FAKE, aux=FAKE, out=FAKE, layout=0, acc=None,
        **kw):
     d = dict(N=1, C_in=8, H=4, W=4, C_out=8, R=3, S=3, stride=1, pad=1, bits=4)

@@ -208,20 +208,19 @@ def test_binary_layer_is_the_convolution_of_signs(kernel):
 
 
 @pytest.mark.parametrize("kernel", [0, 1, 3])
-@pytest.mark.parametrize("bits_a,bits_w", [(4, 3), (3, 4), (2, 1), (1, 2)])
-def test_mixed_widths_inside_one_container_class(bits_a, bits_w, kernel):
-    """Weights and activations may use different widths as long as they share a
-    container (3/4-bit or 1/2-bit): dsq_pack_weights is given the weights' width,
-    dsq_quantize_act and the layer descriptor the activations'."""
+@pytest.mark.parametrize("bits_a,bits_w", [(4, 3), (3, 4), (2, 1), (1, 2), (4, 2), (4, 1), (3, 2), (3, 1)])
+def test_mixed_widths(bits_a, bits_w, kernel):
+    """Weights and activations of different widths: dsq_pack_weights_for is given
+    both, dsq_quantize_act and the layer descriptor the activations'."""
     layer, inp = inputs.small_random_case(31, 2, 128, 7, 6, 72, 3, 1, 1, bits_a, l_a=0.0, u_a=2.2)
     L = layer
     buf = B.alloc_layer(L.N, L.C_in, L.H, L.W, L.C_out, 3, 3, 1, 1, bits_a, with_acc=True)
     xd = inp["x"].permute(0, 2, 3, 1).contiguous().cuda()
     B.dsq_quantize_act(xd, B.DSQ_NHWC, L.N, L.C_in, L.H, L.W, inp["l_a"], inp["u_a"], bits_a,
                        buf.act_packed, buf.pix_code_sum)
-    B.dsq_pack_weights(inp["w"].contiguous().cuda(), torch.from_numpy(inp["l_w"]).cuda(),
-                       torch.from_numpy(inp["u_w"]).cuda(), None, L.C_out, L.C_in, 3, 3, bits_w,
-                       buf.w_packed, buf.w_aux)
+    B.dsq_pack_weights_for(inp["w"].contiguous().cuda(), torch.from_numpy(inp["l_w"]).cuda(),
+                           torch.from_numpy(inp["u_w"]).cuda(), None, L.C_out, L.C_in, 3, 3, bits_w, bits_a,
+                           buf.w_packed, buf.w_aux)
     prev = B.dsq_set_conv_kernel(kernel)
     try:
         B.dsq_conv2d(buf.desc, buf.act_packed, buf.pix_code_sum, inp["l_a"], inp["u_a"], buf.w_packed, buf.w_aux,
