@@ -85,6 +85,7 @@ typedef enum {
     DSQ_ERR_SHAPE = 4,       /* a dimension <= 0, or Ho/Wo <= 0 */
     DSQ_ERR_UNSUPPORTED = 5, /* R != S, R not in {1,3}, stride not in {1,2},
                                 pad > R-1, a tensor of 2^31 or more elements,
+                                R*S*C_in (C_in rounded up to 64) above 2^22 / 9,
                                 unknown layout */
     DSQ_ERR_ALIGN = 6,       /* device pointer not 16-byte aligned */
     DSQ_ERR_SIZE = 7,        /* a caller buffer is smaller than required */

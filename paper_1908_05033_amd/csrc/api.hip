@@ -123,6 +123,10 @@ dsq_status conv_args(const dsq_conv_desc *d, const void *act_packed, const int32
     if (Ho <= 0 || Wo <= 0) return DSQ_ERR_SHAPE;
     const int Cp = dsq_round_up(d->C_in, 64), Cop = dsq_round_up(d->C_out, 256);
     if ((long long)d->N * d->H * d->W * Cp > kMaxElems) return DSQ_ERR_UNSUPPORTED;
+    // depth of the dot products: 9 * K <= 2^22 keeps the fp32 accumulation of the
+    // 1/2-bit path exact (sums of quarter units below 2^24) and the int32 sums of the
+    // 3/4-bit path (at most 225 * K) far from overflow
+    if (9LL * d->R * d->S * Cp > (1LL << 22)) return DSQ_ERR_UNSUPPORTED;
     if ((long long)d->N * Ho * Wo * dsq_round_up(d->C_out, 64) > kMaxElems) return DSQ_ERR_UNSUPPORTED;
     if ((long long)d->N * Ho * Wo + 1024 > kMaxElems) return DSQ_ERR_UNSUPPORTED;
     if (!aligned16(act_packed) || !aligned16(pix_code_sum) || !aligned16(w_packed) || !aligned16(w_aux))

@@ -116,6 +116,7 @@ def test_conv2d_rejects_bad_arguments():
     assert _c(stride=3) == 5 and _c(pad=3) == 5 and _c(R=1, S=1, pad=1) == 5
     assert _c(layout=3) == 5
     assert _c(N=64, H=1024, W=1024, C_in=64) == 5
+    assert _c(H=3, W=3, C_in=51840) == 5          # 9 * 9 * C_in above 2^22: dot products too deep
     assert _c(out=FAKE + 4) == 6 and _c(acc=FAKE + 4) == 6
 
 

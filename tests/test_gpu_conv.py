@@ -190,6 +190,25 @@ def test_largest_codes_at_the_largest_k(bits, kernel):
     assert np.array_equal(got["acc"], acc)
 
 
+@pytest.mark.parametrize("kernel", [0, 1])
+@pytest.mark.parametrize("bits", [1, 2, 3, 4])
+def test_largest_codes_at_the_deepest_dot_product_the_library_accepts(bits, kernel):
+    """K = 9 * 51 712 is the deepest the library takes (9 * K <= 2^22).  With every
+    code at its maximum the accumulator of the centre pixel is top^2 * K: 4.19 M at
+    2 bits, still an exact integer in the FP4 path's fp32 accumulators (quarter
+    units below 2^24), 104.7 M at 4 bits in int32."""
+    top = (1 << bits) - 1
+    C_in = 51712
+    layer, inp = inputs.small_random_case(5, 1, C_in, 3, 3, 32, 3, 1, 1, bits, l_a=0.0, u_a=2.0, asym_w=False)
+    inp["x"] = torch.full_like(inp["x"], 5.0)
+    w_codes = np.full((32, C_in, 3, 3), top, dtype=np.uint8)
+    got = _run(layer, inp, kernel, w_codes=w_codes)
+    a_code, _ = oracle_layer(layer, inp, w_codes)
+    acc = oracle.conv_codes(a_code, w_codes, 1, 1)
+    assert acc.max() == top * top * 9 * C_in
+    assert np.array_equal(got["acc"], acc)
+
+
 @pytest.mark.parametrize("kernel", [0, 1, 3, 4, 6])
 def test_binary_layer_is_the_convolution_of_signs(kernel):
     """bits = 1 with (l, u) = (-1, +1) is the binary quantizer of Sec. 3.1
