@@ -5,7 +5,7 @@ import pytest
 import torch
 
 import oracle
-from helpers import assert_out_close, oracle_layer, run_layer_gpu
+from helpers import assert_out_close, oracle_layer, run_layer_gpu, unpack_act
 from paper_1908_05033_amd import binding as B
 from paper_1908_05033_amd import inputs
 
@@ -257,3 +257,78 @@ def test_mixed_widths(bits_a, bits_w, kernel):
     ref = oracle.conv_dequantized(a_hat, w_hat, 1, 1)
     dw = [oracle.delta(float(a), float(b), bits_w) for a, b in zip(inp["l_w"], inp["u_w"])]
     assert_out_close(buf.out.cpu().numpy().transpose(0, 3, 1, 2), ref, oracle.delta(inp["l_a"], inp["u_a"], bits_a), dw)
+
+
+@pytest.mark.parametrize("kernel", [0, 1])
+def test_largest_tensors_the_library_accepts(kernel):
+    """A 1x1 layer whose input and output both have just under 2^31 elements
+    (33.5 M pixels of 64 channels, 8.6 GB of fp32 output, as much again of raw
+    accumulators): addressing at the size limit.  Every pixel of a 1x1 layer
+    stands alone, so the oracle checks a sample of them: the first and the last
+    rows of the tensor and 4096 pixels in between."""
+    bits = 4
+    N, H, W, C = 1, 32768, 1023, 64
+    P = N * H * W
+    assert P * C < (1 << 31) <= N * H * (W + 1) * C
+    g = torch.Generator(device="cuda").manual_seed(inputs.BASE_SEED + 77)
+    x = torch.empty((P, C), dtype=torch.float32, device="cuda")
+    for s in range(0, P, 1 << 21):
+        x[s:s + (1 << 21)].normal_(0.4, 1.0, generator=g)
+    l_a, u_a = 0.0, float(np.float32(2.75))
+    gw = torch.Generator().manual_seed(inputs.BASE_SEED + 78)
+    w = torch.randn((C, C, 1, 1), generator=gw) * 0.1
+    uw = w.reshape(C, -1).abs().max(dim=1).values.numpy().astype(np.float32)
+    lw = (-0.9 * uw).astype(np.float32)
+    buf = B.alloc_layer(N, C, H, W, C, 1, 1, 1, 0, bits, with_acc=True)
+    B.dsq_quantize_act(x, B.DSQ_NHWC, N, C, H, W, l_a, u_a, bits, buf.act_packed, buf.pix_code_sum)
+    B.dsq_pack_weights(w.cuda(), torch.from_numpy(lw).cuda(), torch.from_numpy(uw).cuda(), None, C, C, 1, 1, bits,
+                       buf.w_packed, buf.w_aux)
+    prev = B.dsq_set_conv_kernel(kernel)
+    try:
+        B.dsq_conv2d(buf.desc, buf.act_packed, buf.pix_code_sum, l_a, u_a, buf.w_packed, buf.w_aux, buf.out,
+                     B.DSQ_NHWC, buf.acc)
+    finally:
+        B.dsq_set_conv_kernel(prev)
+    torch.cuda.synchronize()
+    rs = np.random.RandomState(5)
+    sample = np.unique(np.concatenate([np.arange(2048), np.arange(P - 2048, P), rs.randint(0, P, 4096)]))
+    idx = torch.from_numpy(sample).cuda()
+    xs = x[idx].cpu().numpy().reshape(len(sample), C, 1, 1)             # each sampled pixel as a 1x1 image
+    out = buf.out.reshape(P, C)[idx].cpu().numpy().reshape(len(sample), C, 1, 1)
+    acc = buf.acc.reshape(P, C)[idx].cpu().numpy().reshape(len(sample), C, 1, 1)
+    a_code = oracle.quantize(xs, l_a, u_a, bits)
+    w_code = oracle.quantize_weights(w.numpy(), lw, uw, bits)
+    assert np.array_equal(acc, oracle.conv_codes(a_code, w_code, 1, 0))
+    ref = oracle.conv_real(a_code, l_a, u_a, w_code, lw, uw, bits, 1, 0)
+    dw = [oracle.delta(float(a), float(b), bits) for a, b in zip(lw, uw)]
+    assert_out_close(out, ref, oracle.delta(l_a, u_a, bits), dw)
+    # the chained call on the same tensors: the next layer's codes and pixel sums of the sample
+    scale = (0.5 + torch.rand(C, generator=gw)).numpy().astype(np.float32)
+    shift = (torch.randn(C, generator=gw) * 0.3).numpy().astype(np.float32)
+    l_n, u_n, bits_n = 0.0, float(np.float32(1.9)), 4
+    codes_n = torch.empty((B.dsq_act_packed_bytes(N, H, W, C, bits_n),), dtype=torch.uint8, device="cuda")
+    pix_n = torch.empty((P,), dtype=torch.int32, device="cuda")
+    prev = B.dsq_set_conv_kernel(kernel)
+    try:
+        B.dsq_conv2d_requant(buf.desc, buf.act_packed, buf.pix_code_sum, l_a, u_a, buf.w_packed, buf.w_aux,
+                             torch.from_numpy(scale).cuda(), torch.from_numpy(shift).cuda(), True, l_n, u_n, bits_n,
+                             codes_n, pix_n)
+    finally:
+        B.dsq_set_conv_kernel(prev)
+    torch.cuda.synchronize()
+    want_n = oracle.requantize(ref.astype(np.float32), scale, shift, True, l_n, u_n, bits_n).reshape(len(sample), C)
+    got_rows = codes_n.reshape(P, -1)[idx].cpu().numpy()
+    got_n = unpack_act(got_rows.reshape(-1), len(sample), 1, 1, C, bits_n).reshape(len(sample), -1)[:, :C]
+    # (ref is the oracle's binary64 value; the layer's binary32 output may round to the other side of a
+    # quantizer threshold once in a while: compare where the oracle's own two roundings agree)
+    y32 = out.astype(np.float32)
+    want_from_gpu_y = oracle.requantize(y32, scale, shift, True, l_n, u_n, bits_n).reshape(len(sample), C)
+    assert np.array_equal(got_n, want_from_gpu_y)
+    assert (got_n != want_n).mean() < 1e-3
+    assert np.array_equal(pix_n[idx].cpu().numpy(), want_from_gpu_y.astype(np.int64).sum(axis=1))
+    # nothing was written past the tensors' ends: the last pixel is the sample's last row, and a
+    # pixel row more is refused
+    d2 = B.dsq_conv_desc(N=N, C_in=C, H=H, W=W + 1, C_out=C, R=1, S=1, stride=1, pad=0, bits=bits)
+    with pytest.raises(B.DsqError) as e:
+        B.dsq_conv2d(d2, buf.act_packed, buf.pix_code_sum, l_a, u_a, buf.w_packed, buf.w_aux, buf.out, B.DSQ_NHWC, None)
+    assert e.value.status == 5

@@ -200,3 +200,51 @@ def test_every_float_bit_pattern_gets_the_oracle_code(bits, l, u, layout):
                                      "(first differing pixel %d, codes equal: %s, sums equal: %s)"
                                      % (bits, l, u, start, where, same, sums_same))
             del x, oc, ref
+
+
+def test_largest_tensor_the_library_accepts():
+    """N*H*W*C just below 2^31 elements (8.6 GB of fp32): 64-bit addressing and the
+    pixel bookkeeping at the size limit.  Values are a multiplicative hash of the
+    element index taken as a bit pattern (all kinds of floats); codes and pixel
+    sums are compared with the oracle chunk by chunk."""
+    from concurrent.futures import ThreadPoolExecutor
+    bits, l, u = 4, float(np.float32(-1.25)), float(np.float32(2.5))
+    N, H, W, C = 1, 32768, 1023, 64
+    P = N * H * W
+    total = P * C
+    assert total < (1 << 31) <= N * H * (W + 1) * C
+    x = torch.empty((total,), dtype=torch.float32, device="cuda")
+    CH = 1 << 27
+    for start in range(0, total, CH):
+        n = min(CH, total - start)
+        idx = torch.arange(start, start + n, dtype=torch.int64, device="cuda")
+        v = (idx * 2654435761) & 0xFFFFFFFF
+        x[start:start + n] = torch.where(v >= (1 << 31), v - (1 << 32), v).to(torch.int32).view(torch.float32)
+        del idx, v
+    codes = torch.empty((B.dsq_act_packed_bytes(N, H, W, C, bits),), dtype=torch.uint8, device="cuda")
+    pix = torch.empty((P,), dtype=torch.int32, device="cuda")
+    B.dsq_quantize_act(x, B.DSQ_NHWC, N, C, H, W, l, u, bits, codes, pix)
+    torch.cuda.synchronize()
+    del x
+    workers = 8
+
+    def oracle_part(args):
+        a, b = args
+        v = (np.arange(a, b, dtype=np.uint64) * np.uint64(2654435761)) & np.uint64(0xFFFFFFFF)
+        return oracle.quantize(v.astype(np.uint32).view(np.float32), l, u, bits)
+
+    with ThreadPoolExecutor(workers) as pool:
+        for start in range(0, total, CH):
+            n = min(CH, total - start)
+            cuts = [start + n * k // workers // 64 * 64 for k in range(workers)] + [start + n]
+            want = np.concatenate(list(pool.map(oracle_part, zip(cuts[:-1], cuts[1:]))))
+            oc = torch.from_numpy(want).cuda().reshape(-1, 64)
+            p0, p1 = start // 64, (start + n) // 64
+            ref = pack_codes_reference(oc, bits)
+            assert torch.equal(codes.reshape(P, -1)[p0:p1], ref), "codes differ in pixels %d..%d" % (p0, p1)
+            assert torch.equal(pix[p0:p1], oc.sum(dim=1, dtype=torch.int32)), "sums differ in pixels %d..%d" % (p0, p1)
+            del oc, ref
+    # one more pixel row would pass the limit
+    with pytest.raises(B.DsqError) as e:
+        B.dsq_quantize_act(codes.data_ptr(), B.DSQ_NHWC, N, C, H, W + 1, l, u, bits, codes, pix)
+    assert e.value.status == 5
