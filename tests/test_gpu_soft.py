@@ -69,6 +69,39 @@ def test_backward(l, u, alpha, bits, n):
         assert abs(got - terms.sum()) <= 1e-5 * np.abs(terms).sum() + 1e-12
 
 
+def test_largest_tensor():
+    """n = 2^31 - 1 elements (the limit, and an odd count): forward values and the
+    elementwise gradient at the head, the tail and a million places in between."""
+    l, u, alpha, bits = -1.0, 2.0, 0.2, 4
+    n = (1 << 31) - 1
+    g = torch.Generator(device="cuda").manual_seed(inputs.BASE_SEED + 91)
+    x = torch.empty((n,), dtype=torch.float32, device="cuda")
+    gy = torch.empty((n,), dtype=torch.float32, device="cuda")
+    for s in range(0, n, 1 << 27):
+        x[s:s + (1 << 27)].normal_(0.5, 1.2, generator=g)
+        gy[s:s + (1 << 27)].normal_(0.0, 1.0, generator=g)
+    y = torch.empty_like(x)
+    B.dsq_soft_quantize_fwd(x, l, u, alpha, bits, y)
+    gx = torch.empty_like(x)
+    sums = torch.zeros((4,), dtype=torch.float64, device="cuda")
+    B.dsq_soft_quantize_bwd(x, gy, l, u, alpha, bits, gx, sums)
+    torch.cuda.synchronize()
+    rs = np.random.RandomState(3)
+    sample = np.unique(np.concatenate([np.arange(4096), np.arange(n - 4096, n), rs.randint(0, n, 1 << 20)]))
+    idx = torch.from_numpy(sample).cuda()
+    xs = x[idx].cpu().numpy().astype(np.float64)
+    gs = gy[idx].cpu().numpy().astype(np.float64)
+    lf, uf, af = np.float32(l), np.float32(u), np.float32(alpha)
+    ref = S.forward(xs, lf, uf, af, bits)
+    assert np.abs(y[idx].cpu().numpy() - ref).max() <= 2e-6 * max(abs(l), abs(u), u - l)
+    dx, da, dl, du = S.partials(xs, lf, uf, af, bits)
+    assert np.abs(gx[idx].cpu().numpy() - gs * dx).max() <= 1e-5 * max(1.0, np.abs(dx).max()) * np.abs(gs).max()
+    assert np.isfinite(sums.cpu().numpy()[:3]).all()
+    with pytest.raises(B.DsqError) as e:                      # one element more is refused
+        B._check(B.load_library().dsq_soft_quantize_fwd(x.data_ptr(), n + 1, l, u, alpha, bits, y.data_ptr(), None))
+    assert e.value.status == 4
+
+
 def test_special_values():
     l, u, alpha, bits = -1.0, 2.0, 0.2, 3
     d = (u - l) / 7
