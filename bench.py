@@ -9,9 +9,10 @@ separately and is not part of the step.  The workload is the 3x3, 256->256,
 14x14, batch-32, 4-bit layer (the ResNet stage-3 shape).  Inputs live in HBM
 before the timed region; the steps rotate over enough buffer sets that the
 working set exceeds the 256 MB last-level cache.  By default the steps are dealt
-to four streams (four batches in flight, each running its own quantize -> conv
-in order), which is how a server with several requests in flight drives the
-library; --serial runs them strictly one after the other and is reported too.
+to four chains (four batches in flight, each running its own quantize -> conv
+in order), one hipGraph and one stream per chain, which is how a server with
+several requests in flight drives the library; --serial runs them strictly one
+after the other and is reported too.
 
 Prints ONE JSON line:  value = effective int-TOPS = 2*MACs*steps / time.
 """
@@ -30,7 +31,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per dsq_conv2d launch on this workload from two rocprofv3 --pmc runs
 # (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors from a 256 MiB copy kernel;
 # profiles/traffic_cfg2.md).  Algorithmic bytes are 7.55 MB.
-MEASURED_CONV_TRAFFIC_BYTES = {2: 9955709}
+MEASURED_CONV_TRAFFIC_BYTES = {2: 9955712}
 
 
 def parse_args():
@@ -45,6 +46,8 @@ def parse_args():
     ap.add_argument("--streams", type=int, default=4,
                     help="run the steps as this many independent serial chains, one stream each "
                          "(0 = the two-stream pipeline: quantize of batch i+1 beside conv of batch i)")
+    ap.add_argument("--one-graph", action="store_true",
+                    help="the chains as branches of a single graph instead of one graph per chain")
     return ap.parse_args()
 
 
@@ -155,6 +158,51 @@ def main():
                 stream.wait_stream(st)
         return g
 
+    def capture_chain_graphs(n_chains):
+        """One graph per chain: the steps dealt round-robin to n_chains chains, each
+        captured as a strictly serial graph of its own."""
+        graphs = []
+        for c in range(n_chains):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=stream):
+                for b in bufs[c::n_chains]:
+                    quant(b)
+                    conv(b)
+            graphs.append(g)
+        return graphs
+
+    def timed_chain_replays(graphs, streams, n):
+        """n replays of every chain graph, chain c on streams[c], between two events
+        on the launch stream (which the chain streams wait for and are joined to)."""
+        torch.cuda.synchronize()
+        ev0.record(stream)
+        for st in streams:
+            st.wait_event(ev0)
+        for _ in range(n):
+            for g, st in zip(graphs, streams):
+                with torch.cuda.stream(st):
+                    g.replay()
+        for st in streams:
+            stream.wait_stream(st)
+        ev1.record(stream)
+        torch.cuda.synchronize()
+        return ev0.elapsed_time(ev1) * 1e-3
+
+    def pick_streams(graphs, n_chains):
+        """HIP multiplexes its streams onto a few hardware queues; chains whose
+        streams share a queue run one after the other.  Which streams share one is
+        not visible from here, so a short calibration run tries windows of
+        consecutive streams from a small pool and keeps the fastest."""
+        pool = [torch.cuda.Stream() for _ in range(n_chains + 6)]
+        best, best_t = None, None
+        for o in range(len(pool) - n_chains + 1):
+            cand = pool[o:o + n_chains]
+            timed_chain_replays(graphs, cand, 1)
+            t = min(timed_chain_replays(graphs, cand, 2) for _ in range(2))
+            if best_t is None or t < best_t:
+                best, best_t = cand, t
+        return best
+
     def timed_replays(g, n):
         """n replays of a graph between two events on the launch stream."""
         with torch.cuda.stream(stream):
@@ -185,22 +233,32 @@ def main():
         conv(b)
 
     g_step, g_quant, g_conv = capture(step), capture(quant), capture(conv)
+    chain_graphs = chain_streams = None
     if args.serial:
         g_pipe = g_step
+    elif args.streams > 0 and not args.one_graph:
+        g_pipe = None
+        chain_graphs = capture_chain_graphs(args.streams)
+        chain_streams = pick_streams(chain_graphs, args.streams)
     elif args.streams > 0:
         g_pipe = capture_chains(args.streams)
     else:
         g_pipe = capture_pipelined()
+
+    def timed_pass(n):
+        if chain_graphs is not None:
+            return timed_chain_replays(chain_graphs, chain_streams, n)
+        return timed_replays(g_pipe, n)
 
     # ---- the timed region: exactly `steps` steps ---------------------------
     n_warm = max(1, -(-args.warmup // sets))
     n_rep = max(1, -(-args.steps // sets))
     steps = n_rep * sets
     warmup = n_warm * sets
-    timed_replays(g_pipe, n_warm)
+    timed_pass(n_warm)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    gpu_s = timed_replays(g_pipe, n_rep)
+    gpu_s = timed_pass(n_rep)
     wall_s = time.perf_counter() - t0
     step_s = max(gpu_s, 0.0) / steps
     value = 2.0 * macs / step_s / 1e12
@@ -237,10 +295,15 @@ def main():
             "gemm_MxNxK": [L.N * L.Ho * L.Wo, L.C_out, L.C_in * L.R * L.S],
             "macs_per_step": macs,
             "buffer_sets": sets,
-            "launch": ("hipGraph of %d steps replayed %d times; " % (sets, n_rep)) +
-                      ("steps strictly serial on one stream" if args.serial else
-                       "%d independent chains of serial steps, one stream each" % args.streams if args.streams > 0 else
-                       "quantize of batch i+1 overlaps conv of batch i (two streams)"),
+            "launch": ("%d steps per pass, %d passes; " % (sets, n_rep)) +
+                      ("one hipGraph, steps strictly serial on one stream" if args.serial else
+                       "%d hipGraphs, each a serial chain of every %dth step, replayed side by side on %d streams "
+                       "(picked from a pool of %d by a calibration run: streams that share a hardware queue "
+                       "would serialise)" % (args.streams, args.streams, args.streams, args.streams + 6)
+                       if chain_graphs is not None else
+                       "one hipGraph with %d independent chains of serial steps as branches" % args.streams
+                       if args.streams > 0 else
+                       "one hipGraph, quantize of batch i+1 overlaps conv of batch i (two streams)"),
         },
         "kernels": {
             "serial_step_us": round(serial_step_s * 1e6, 3),
