@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per dsq_conv2d launch on this workload from two rocprofv3 --pmc runs
 # (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors from a 256 MiB copy kernel;
 # profiles/traffic_cfg2.md).  Algorithmic bytes are 7.55 MB.
-MEASURED_CONV_TRAFFIC_BYTES = {2: 9955712}
+MEASURED_CONV_TRAFFIC_BYTES = {2: 9954684}
 
 
 def parse_args():
@@ -46,6 +46,9 @@ def parse_args():
     ap.add_argument("--streams", type=int, default=4,
                     help="run the steps as this many independent serial chains, one stream each "
                          "(0 = the two-stream pipeline: quantize of batch i+1 beside conv of batch i)")
+    ap.add_argument("--latency-policy", action="store_true",
+                    help="keep the library's default kernel choice (shortest single call) although several "
+                         "steps are in flight; the default here is dsq_set_conv_policy(1)")
     ap.add_argument("--one-graph", action="store_true",
                     help="the chains as branches of a single graph instead of one graph per chain")
     return ap.parse_args()
@@ -66,6 +69,10 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     B.load_library()
+    # several batches in flight: tell the library (it then spreads a layer differently);
+    # every figure of this run, the kernel durations included, is taken under the same policy
+    many_in_flight = not args.serial and not args.latency_policy
+    B.dsq_set_conv_policy(1 if many_in_flight else 0)
 
     layer, inp = inputs.make_config_layer(args.config)
     L = layer
@@ -272,6 +279,13 @@ def main():
     timed_replays(g_quant, n_warm)
     quant_s = timed_replays(g_quant, n_rep) / steps
 
+    # the same kernel call under the other policy, for the record
+    B.dsq_set_conv_policy(0 if many_in_flight else 1)
+    g_conv_other = capture(conv)
+    B.dsq_set_conv_policy(1 if many_in_flight else 0)
+    timed_replays(g_conv_other, n_warm)
+    conv_other_s = timed_replays(g_conv_other, n_rep) / steps
+
     conv_tops = 2.0 * macs / conv_s / 1e12
     quant_bytes = in_bytes + code_bytes + L.N * L.H * L.W * 4
     result = {
@@ -295,6 +309,8 @@ def main():
             "gemm_MxNxK": [L.N * L.Ho * L.Wo, L.C_out, L.C_in * L.R * L.S],
             "macs_per_step": macs,
             "buffer_sets": sets,
+            "kernel_policy": "dsq_set_conv_policy(1): several calls in flight" if many_in_flight else
+                             "dsq_set_conv_policy(0): shortest single call",
             "launch": ("%d steps per pass, %d passes; " % (sets, n_rep)) +
                       ("one hipGraph, steps strictly serial on one stream" if args.serial else
                        "%d hipGraphs, each a serial chain of every %dth step, replayed side by side on %d streams "
@@ -309,6 +325,7 @@ def main():
             "serial_step_us": round(serial_step_s * 1e6, 3),
             "dsq_conv2d_us": round(conv_s * 1e6, 3),
             "dsq_conv2d_TOPS": round(conv_tops, 2),
+            "dsq_conv2d_us_under_policy_%d" % (0 if many_in_flight else 1): round(conv_other_s * 1e6, 3),
             "dsq_quantize_act_us": round(quant_s * 1e6, 3),
             "dsq_quantize_act_GBps": round(quant_bytes / quant_s / 1e9, 1),
             "dsq_pack_weights_us_not_in_step": round(pack_ms * 1e3, 2),

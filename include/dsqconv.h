@@ -257,10 +257,21 @@ dsq_status dsq_soft_quantize_bwd(const float *x, const float *grad_y, size_t n,
  * 256x128 / 256x64 (pixels x channels) tile.  With 2..6, dsq_conv2d returns
  * DSQ_ERR_UNSUPPORTED instead of falling back when the patch kernel cannot
  * take the geometry (the 256x128 tile has no dsq_conv2d_requant variant and
- * reports the same).  For tests and benchmarking; this selector is the only
- * state the library keeps; process-wide, not thread-safe.  Returns the
- * previous value; values outside 0..6 change nothing. */
+ * reports the same).  For tests and benchmarking; this selector and the
+ * policy below are the only state the library keeps; process-wide, not
+ * thread-safe.  Returns the previous value; values outside 0..6 change
+ * nothing. */
 int dsq_set_conv_kernel(int which);
+
+/* What the automatic kernel choice optimises for.  0 (default): the shortest
+ * time of a single call on an otherwise idle GPU -- layers that yield only
+ * about one workgroup per compute unit run with two wave groups per workgroup.
+ * 1: the highest throughput when the caller keeps several calls in flight on
+ * different streams (a server with several requests, several layers of
+ * independent branches) -- one wave group per workgroup, so that workgroups
+ * of different calls share the compute units.  Results are identical either
+ * way.  Returns the previous value; other values change nothing. */
+int dsq_set_conv_policy(int policy);
 
 /* Static, NUL-terminated description of a status code. */
 const char *dsq_status_string(dsq_status s);

@@ -22,7 +22,7 @@ EXPORTS = [
     "dsq_act_packed_bytes", "dsq_wgt_packed_bytes", "dsq_wgt_aux_bytes",
     "dsq_quantize_act", "dsq_pack_weights", "dsq_pack_weights_for", "dsq_conv2d", "dsq_conv2d_requant",
     "dsq_soft_quantize_fwd", "dsq_soft_quantize_bwd",
-    "dsq_set_conv_kernel", "dsq_status_string",
+    "dsq_set_conv_kernel", "dsq_set_conv_policy", "dsq_status_string",
 ]
 
 
@@ -75,6 +75,8 @@ def load_library():
     lib.dsq_soft_quantize_bwd.argtypes = [vp, vp, sz, f, f, f, i, vp, vp, vp]
     lib.dsq_set_conv_kernel.restype = i
     lib.dsq_set_conv_kernel.argtypes = [i]
+    lib.dsq_set_conv_policy.restype = i
+    lib.dsq_set_conv_policy.argtypes = [i]
     lib.dsq_status_string.restype = C.c_char_p
     lib.dsq_status_string.argtypes = [i]
     _lib = lib
@@ -186,6 +188,10 @@ def dsq_soft_quantize_bwd(x, grad_y, l, u, alpha, bits, grad_x, grad_alpha_l_u, 
 
 def dsq_set_conv_kernel(which):
     return int(load_library().dsq_set_conv_kernel(which))
+
+
+def dsq_set_conv_policy(policy):
+    return int(load_library().dsq_set_conv_policy(policy))
 
 
 # ---------------------------------------------------------------------------

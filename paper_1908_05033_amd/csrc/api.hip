@@ -10,6 +10,7 @@
 namespace {
 
 int g_conv_kernel = 0;   // 0 auto, 1 simple, 2 patch (auto tile), 3..6 patch with a fixed tile
+int g_conv_policy = 0;   // 0: shortest single call, 1: several calls in flight
 
 bool bits_ok(int bits) { return bits >= 1 && bits <= 4; }
 bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
@@ -136,6 +137,7 @@ dsq_status conv_args(const dsq_conv_desc *d, const void *act_packed, const int32
     a.stride = d->stride; a.pad = d->pad; a.bits = d->bits;
     a.Ho = Ho; a.Wo = Wo; a.Cp = Cp; a.Cop = Cop;
     a.act = act_packed; a.pix_sum = pix_code_sum; a.l_a = l_a; a.u_a = u_a;
+    a.many_in_flight = g_conv_policy;
     // (one IEEE binary32 subtraction and division: the value dsq_delta gives on the device)
     a.delta_a = (u_a - l_a) / (float)((1 << d->bits) - 1);
     a.wq = w_packed;
@@ -327,6 +329,13 @@ int dsq_set_conv_kernel(int which)
 {
     int prev = g_conv_kernel;
     if (which >= 0 && which <= 6) g_conv_kernel = which;
+    return prev;
+}
+
+int dsq_set_conv_policy(int policy)
+{
+    int prev = g_conv_policy;
+    if (policy == 0 || policy == 1) g_conv_policy = policy;
     return prev;
 }
 

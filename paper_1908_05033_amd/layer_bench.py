@@ -146,7 +146,10 @@ def main():
     ap.add_argument("--kernel", type=int, default=0)
     ap.add_argument("--layer", type=int, default=None)
     ap.add_argument("--chained", action="store_true")
+    ap.add_argument("--policy", type=int, default=0,
+                    help="dsq_set_conv_policy value (0 = shortest single call: kernels are timed one at a time here)")
     a = ap.parse_args()
+    B.dsq_set_conv_policy(a.policy)
     layers = inputs.config_layers(a.cfg, a.bits)
     if a.layer is not None:
         layers = [layers[a.layer]]

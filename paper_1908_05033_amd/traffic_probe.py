@@ -24,7 +24,10 @@ def main():
     ap.add_argument("--cfg", type=int, default=2)
     ap.add_argument("--layer", type=int, default=0)
     ap.add_argument("--sets", type=int, default=48)
+    ap.add_argument("--policy", type=int, default=1,
+                    help="dsq_set_conv_policy value (1 = several calls in flight, what bench.py runs with)")
     a = ap.parse_args()
+    B.dsq_set_conv_policy(a.policy)
     L = inputs.config_layers(a.cfg)[a.layer]
     dev = "cuda"
     gen = torch.Generator(device=dev).manual_seed(inputs.BASE_SEED)

@@ -134,6 +134,13 @@ def test_kernel_selector_roundtrip():
     assert B.dsq_set_conv_kernel(prev) == prev
 
 
+def test_policy_roundtrip():
+    prev = B.dsq_set_conv_policy(1)
+    assert B.dsq_set_conv_policy(prev) == 1
+    assert B.dsq_set_conv_policy(7) == prev       # out of range: unchanged
+    assert B.dsq_set_conv_policy(prev) == prev
+
+
 def _r(desc=None, act=FAKE, pix=FAKE, la=0.0, ua=1.0, wp=FAKE, aux=FAKE, scale=None, shift=None, relu=1,
        ln=0.0, un=1.0, bn=4, codes=FAKE, nbytes=1 << 20, pixn=FAKE, **kw):
     d = dict(N=1, C_in=8, H=4, W=4, C_out=8, R=3, S=3, stride=1, pad=1, bits=4)

@@ -332,3 +332,22 @@ def test_largest_tensors_the_library_accepts(kernel):
     with pytest.raises(B.DsqError) as e:
         B.dsq_conv2d(d2, buf.act_packed, buf.pix_code_sum, l_a, u_a, buf.w_packed, buf.w_aux, buf.out, B.DSQ_NHWC, None)
     assert e.value.status == 5
+
+
+@pytest.mark.parametrize("geom", [(2, 256, 14, 14, 256, 3, 1, 1), (1, 512, 7, 7, 512, 3, 1, 1), (2, 128, 9, 11, 96, 3, 2, 1),
+                                  (1, 576, 6, 6, 96, 1, 1, 0)])
+@pytest.mark.parametrize("bits", [2, 4])
+def test_throughput_policy_gives_the_same_results(geom, bits):
+    """dsq_set_conv_policy(1) only changes how a layer is spread over the chip
+    (one wave group per workgroup where the default uses two): accumulators and
+    outputs of layers that the default runs with two groups must not change."""
+    N, Ci, H, W, Co, R, stride, pad = geom
+    layer, inp = inputs.small_random_case(41 + bits, N, Ci, H, W, Co, R, stride, pad, bits, l_a=0.0, u_a=2.1)
+    prev = B.dsq_set_conv_policy(1)
+    try:
+        got, ref = _check_full(layer, inp, 0)
+        got_rq = None
+    finally:
+        B.dsq_set_conv_policy(prev)
+    base = _run(layer, inp, 0)
+    assert np.array_equal(got["acc"], base["acc"]) and np.array_equal(got["out"], base["out"])
