@@ -254,13 +254,15 @@ dsq_status dsq_soft_quantize_bwd(const float *x, const float *grad_y, size_t n,
 /* Selects the convolution kernel: 0 = automatic (default), 1 = the simple
  * one-wave-per-tile kernel, 2 = the LDS-patch kernel with its tile chosen by
  * problem size, 3 / 4 / 5 / 6 = the LDS-patch kernel with the 128x64 / 128x128 /
- * 256x128 / 256x64 (pixels x channels) tile.  With 2..6, dsq_conv2d returns
- * DSQ_ERR_UNSUPPORTED instead of falling back when the patch kernel cannot
- * take the geometry (the 256x128 tile has no dsq_conv2d_requant variant and
- * reports the same).  For tests and benchmarking; this selector and the
- * policy below are the only state the library keeps; process-wide, not
- * thread-safe.  Returns the previous value; values outside 0..6 change
- * nothing. */
+ * 256x128 / 256x64 (pixels x channels) tile, 7 = the split-K kernel for 1x1
+ * layers with few output pixels and at least 512 input channels (fully
+ * connected layers; taken automatically for those).  With 2..7, dsq_conv2d
+ * returns DSQ_ERR_UNSUPPORTED instead of falling back when the chosen kernel
+ * cannot take the geometry (the 256x128 tile and the split-K kernel have no
+ * dsq_conv2d_requant variant and report the same).  For tests and
+ * benchmarking; this selector and the policy below are the only state the
+ * library keeps; process-wide, not thread-safe.  Returns the previous value;
+ * values outside 0..7 change nothing. */
 int dsq_set_conv_kernel(int which);
 
 /* What the automatic kernel choice optimises for.  0 (default): the shortest

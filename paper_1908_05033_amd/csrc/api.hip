@@ -9,7 +9,7 @@
 
 namespace {
 
-int g_conv_kernel = 0;   // 0 auto, 1 simple, 2 patch (auto tile), 3..6 patch with a fixed tile
+int g_conv_kernel = 0;   // 0 auto, 1 simple, 2 patch (auto tile), 3..6 patch with a fixed tile, 7 split-K 1x1
 int g_conv_policy = 0;   // 0: shortest single call, 1: several calls in flight
 
 bool bits_ok(int bits) { return bits >= 1 && bits <= 4; }
@@ -199,6 +199,14 @@ void quantizer_thresholds(float l, float u, int bits, float thr[16])
 dsq_status launch_conv(const DsqConvArgs &a, hipStream_t stream)
 {
     hipError_t e;
+    if (g_conv_kernel == 7 || g_conv_kernel == 0) {
+        const bool fc_ok = dsq_conv_fc_supported(a);
+        if (g_conv_kernel == 7 && !fc_ok) return DSQ_ERR_UNSUPPORTED;
+        if (fc_ok) {
+            e = dsq_launch_conv_fc(a, stream);
+            return e == hipSuccess ? DSQ_OK : DSQ_ERR_HIP;
+        }
+    }
     const int force_tile = g_conv_kernel >= 3 ? g_conv_kernel - 3 : -1;
     const bool patch_ok = g_conv_kernel != 1 && dsq_conv_patch_supported(a, force_tile);
     if (g_conv_kernel >= 2 && !patch_ok) return DSQ_ERR_UNSUPPORTED;
@@ -328,7 +336,7 @@ dsq_status dsq_soft_quantize_bwd(const float *x, const float *grad_y, size_t n, 
 int dsq_set_conv_kernel(int which)
 {
     int prev = g_conv_kernel;
-    if (which >= 0 && which <= 6) g_conv_kernel = which;
+    if (which >= 0 && which <= 7) g_conv_kernel = which;
     return prev;
 }
 

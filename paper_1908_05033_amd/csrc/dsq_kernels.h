@@ -88,3 +88,7 @@ hipError_t dsq_launch_conv_simple(const DsqConvArgs &a, hipStream_t stream);
 hipError_t dsq_launch_conv_patch(const DsqConvArgs &a, int force_tile, hipStream_t stream);
 // Whether the LDS-patch kernel supports this geometry with that tile.
 bool dsq_conv_patch_supported(const DsqConvArgs &a, int force_tile);
+
+// Split-K kernel for 1x1 layers with few output pixels (fully connected layers).
+bool dsq_conv_fc_supported(const DsqConvArgs &a);
+hipError_t dsq_launch_conv_fc(const DsqConvArgs &a, hipStream_t stream);

@@ -1,6 +1,7 @@
 """Per-layer timing of dsq_quantize_act and dsq_conv2d on one GPU.
 
     python -m paper_1908_05033_amd.layer_bench --cfg 3 [--bits 4] [--kernel 0] [--chained]
+    python -m paper_1908_05033_amd.layer_bench --fc [--kernel 2]      (fully connected layers)
 
 For every layer of a config (shapes from :mod:`paper_1908_05033_amd.inputs`)
 it prints one JSON line: kernel time, effective int-TOPS (2*MACs/s, padding taps
@@ -141,7 +142,9 @@ def bench_layer(L, kernel=0, min_bytes=600e6, max_sets=16, reps=5, chained=False
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--cfg", type=int, required=True)
+    ap.add_argument("--cfg", type=int, default=None)
+    ap.add_argument("--fc", action="store_true",
+                    help="fully connected layers (1x1 layers on 1x1 images) instead of a benchmark config")
     ap.add_argument("--bits", type=int, default=None)
     ap.add_argument("--kernel", type=int, default=0)
     ap.add_argument("--layer", type=int, default=None)
@@ -150,7 +153,14 @@ def main():
                     help="dsq_set_conv_policy value (0 = shortest single call: kernels are timed one at a time here)")
     a = ap.parse_args()
     B.dsq_set_conv_policy(a.policy)
-    layers = inputs.config_layers(a.cfg, a.bits)
+    if a.fc:
+        layers = [inputs.ConvLayer("fc.%d-%d@batch%d" % (ci, co, n), n, ci, 1, 1, co, 1, 1, 1, 0, b)
+                  for n, ci, co, b in ((64, 4096, 4096, 4), (64, 4096, 4096, 2), (256, 4096, 4096, 4),
+                                       (64, 25088, 4096, 4), (64, 4096, 1000, 4), (1024, 4096, 4096, 4))]
+    else:
+        if a.cfg is None:
+            ap.error("--cfg or --fc")
+        layers = inputs.config_layers(a.cfg, a.bits)
     if a.layer is not None:
         layers = [layers[a.layer]]
     tot_t, tot_macs = 0.0, 0
@@ -159,7 +169,7 @@ def main():
         print(json.dumps(r), flush=True)
         tot_t += (r["conv_us"] + r["quant_us"]) * 1e-6 * L.count
         tot_macs += L.macs * L.count
-    print(json.dumps({"config": a.cfg, "layers": sum(L.count for L in layers),
+    print(json.dumps({"config": "fc" if a.fc else a.cfg, "layers": sum(L.count for L in layers),
                       "total_GMAC": round(tot_macs / 1e9, 2),
                       "quant_plus_conv_ms": round(tot_t * 1e3, 3),
                       "TOPS_over_quant_plus_conv": round(2 * tot_macs / tot_t / 1e12, 1)}))

@@ -351,3 +351,44 @@ def test_throughput_policy_gives_the_same_results(geom, bits):
         B.dsq_set_conv_policy(prev)
     base = _run(layer, inp, 0)
     assert np.array_equal(got["acc"], base["acc"]) and np.array_equal(got["out"], base["out"])
+
+
+FC_SHAPES = [  # N, C_in, H, W, C_out : 1x1 layers with few pixels and a deep dot product
+    (64, 4096, 1, 1, 1000),
+    (5, 520, 1, 1, 37),
+    (2, 1024, 3, 2, 70),
+    (256, 512, 1, 1, 96),
+    (33, 2304, 1, 1, 128),
+]
+
+
+@pytest.mark.parametrize("kernel", [0, 7])
+@pytest.mark.parametrize("bits", [1, 2, 3, 4])
+@pytest.mark.parametrize("shape", FC_SHAPES)
+def test_fully_connected_shapes(shape, bits, kernel):
+    """The split-K kernel (taken automatically for these shapes, and forced):
+    accumulators bit-exact, outputs to tolerance, with and without the raw
+    accumulator output."""
+    N, Ci, H, W, Co = shape
+    layer, inp = inputs.small_random_case(sum(shape) + bits, N, Ci, H, W, Co, 1, 1, 0, bits, l_a=0.0, u_a=2.3)
+    _check_full(layer, inp, kernel)
+
+
+@pytest.mark.parametrize("out_layout", [B.DSQ_NHWC, B.DSQ_NCHW])
+@pytest.mark.parametrize("bits", [2, 4])
+def test_fully_connected_general_epilogue(bits, out_layout):
+    """l_a != 0 and NCHW output through the split-K kernel."""
+    layer, inp = inputs.small_random_case(17 + bits, 9, 768, 2, 2, 50, 1, 1, 0, bits, l_a=-0.6, u_a=1.9)
+    got = run_layer_gpu(layer, inp, kernel=7, out_layout=out_layout)
+    a_code, w_code = oracle_layer(layer, inp)
+    assert np.array_equal(got["acc"], oracle.conv_codes(a_code, w_code, 1, 0))
+    ref = oracle.conv_real(a_code, inp["l_a"], inp["u_a"], w_code, inp["l_w"], inp["u_w"], bits, 1, 0)
+    dw = [oracle.delta(float(a), float(b), bits) for a, b in zip(inp["l_w"], inp["u_w"])]
+    assert_out_close(got["out"], ref, oracle.delta(inp["l_a"], inp["u_a"], bits), dw)
+
+
+def test_split_k_kernel_refuses_other_layers():
+    layer, inp = inputs.small_random_case(3, 2, 64, 5, 5, 32, 3, 1, 1, 4)
+    with pytest.raises(B.DsqError) as e:
+        run_layer_gpu(layer, inp, kernel=7)
+    assert e.value.status == 5
