@@ -359,6 +359,8 @@ FC_SHAPES = [  # N, C_in, H, W, C_out : 1x1 layers with few pixels and a deep do
     (2, 1024, 3, 2, 70),
     (256, 512, 1, 1, 96),
     (33, 2304, 1, 1, 128),
+    (100, 640, 1, 1, 45),          # two pixel fragments per workgroup, the second one ragged
+    (3, 576, 5, 9, 64),            # 135 pixels
 ]
 
 
