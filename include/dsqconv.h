@@ -258,8 +258,8 @@ dsq_status dsq_soft_quantize_bwd(const float *x, const float *grad_y, size_t n,
  * layers with few output pixels and at least 512 input channels (fully
  * connected layers; taken automatically for those).  With 2..7, dsq_conv2d
  * returns DSQ_ERR_UNSUPPORTED instead of falling back when the chosen kernel
- * cannot take the geometry (the 256x128 tile and the split-K kernel have no
- * dsq_conv2d_requant variant and report the same).  For tests and
+ * cannot take the geometry (the 256x128 tile has no dsq_conv2d_requant
+ * variant and reports the same).  For tests and
  * benchmarking; this selector and the policy below are the only state the
  * library keeps; process-wide, not thread-safe.  Returns the previous value;
  * values outside 0..7 change nothing. */

@@ -54,7 +54,7 @@ __global__ __launch_bounds__(64 * FC_WAVES) void conv_fc_kernel(DsqConvArgs a)
     const int M = a.N * a.Ho * a.Wo;             // = N*H*W: 1x1, stride 1, no padding
     const int m0 = blockIdx.x * 32;
     const int m = m0 + col;
-    const int ct = blockIdx.y;                   // 32-channel tile; ct*32 < Cop by construction
+    const int ct = blockIdx.y;                   // 32-channel tile; ct*32 < Cop by construction (Cop >= rq_Cp)
     const int NCB = a.Cp / 64;
     const size_t row_bytes = (size_t)a.Cp * CONT / 8;
     const uint32_t *wq = (const uint32_t *)a.wq + ((size_t)ct * NCB * 64 + lane) * 4;
@@ -127,6 +127,27 @@ __global__ __launch_bounds__(64 * FC_WAVES) void conv_fc_kernel(DsqConvArgs a)
     for (int q = 0; q < 4; ++q)
         part[(wave * 4 + q) * 64 + lane] = (v4i){acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
     __syncthreads();
+    if (a.rq) {
+        // chained mode: one wave needs the whole tile (a lane pair holds whole
+        // packed words of its pixel); the next layer's codes and pixel sums
+        if (wave == 0) {
+            v16i tot;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                v4i sum = part[q * 64 + lane];
+#pragma unroll
+                for (int w = 1; w < FC_WAVES; ++w) {
+                    const v4i t = part[(w * 4 + q) * 64 + lane];
+                    sum.x += t.x; sum.y += t.y; sum.z += t.z; sum.w += t.w;
+                }
+                tot[4 * q] = sum.x; tot[4 * q + 1] = sum.y; tot[4 * q + 2] = sum.z; tot[4 * q + 3] = sum.w;
+            }
+            const DsqPixel px = dsq_pixel_info(a, m, M);
+            const int total = dsq_requant_tile(a, px, m, ct * 32, h, tot, a.delta_a);
+            if (h == 0 && px.valid) atomicAdd(a.rq_pix + m, total);
+        }
+        return;
+    }
     if (wave < 4) {
         const int q = wave;
         v4i sum = part[q * 64 + lane];
@@ -150,18 +171,19 @@ hipError_t launch_fc(const DsqConvArgs &a, hipStream_t stream)
         if (e != hipSuccess) return e;
     }
     const int M = a.N * a.Ho * a.Wo;
-    dim3 grid((M + 31) / 32, (a.C_out + 31) / 32);
+    // (chained mode also writes the code-0 padding channels up to a multiple of 64)
+    dim3 grid((M + 31) / 32, ((a.rq ? a.rq_Cp : a.C_out) + 31) / 32);
     kern<<<grid, 64 * FC_WAVES, lds, stream>>>(a);
     return hipGetLastError();
 }
 
 }  // namespace
 
-// 1x1, stride 1, no padding, no chained output; few enough 32x32 tiles that splitting K
-// inside the workgroup pays, and K deep enough to split.
+// 1x1, stride 1, no padding; few enough 32x32 tiles that splitting K inside the
+// workgroup pays, and K deep enough to split.
 bool dsq_conv_fc_supported(const DsqConvArgs &a)
 {
-    if (a.R != 1 || a.stride != 1 || a.pad != 0 || a.rq) return false;
+    if (a.R != 1 || a.stride != 1 || a.pad != 0) return false;
     const long long M = (long long)a.N * a.Ho * a.Wo;
     const long long tiles = ((M + 31) / 32) * ((a.C_out + 31) / 32);
     return a.Cp >= 512 && tiles <= 2048;

@@ -125,6 +125,26 @@ def test_small_geometries(geom, bits, bits_n, l_a, relu, kernel):
     assert np.array_equal(pix, got.astype(np.int64).sum(axis=3))
 
 
+FC_SHAPES = [(64, 1024, 1, 1, 1000), (5, 520, 1, 1, 37), (2, 1024, 3, 2, 70), (40, 2304, 1, 1, 128)]
+
+
+@pytest.mark.parametrize("kernel", [0, 7])
+@pytest.mark.parametrize("l_a,relu", [(0.0, True), (-0.4, False)])
+@pytest.mark.parametrize("bits,bits_n", [(4, 4), (2, 2), (3, 2), (1, 4)])
+@pytest.mark.parametrize("shape", FC_SHAPES)
+def test_fully_connected_shapes(shape, bits, bits_n, l_a, relu, kernel):
+    """The split-K kernel's chained mode (automatic for these shapes, and forced)."""
+    N, Ci, H, W, Co = shape
+    layer, inp = inputs.small_random_case(sum(shape) + bits, N, Ci, H, W, Co, 1, 1, 0, bits, l_a=l_a, u_a=2.1)
+    scale, shift = inputs.affine_params(sum(shape), Co)
+    y, z, _ = oracle_requant(layer, inp, scale, shift, relu, 0.0, 1.0, bits_n)
+    l_n, u_n = next_range(z, relu)
+    want = oracle.quantize(z, l_n, u_n, bits_n)
+    got, pix, *_ = run_requant_gpu(layer, inp, scale, shift, relu, l_n, u_n, bits_n, kernel, skip_unsupported=False)
+    assert_codes_match(got, want, z, l_n, u_n, bits_n, Co)
+    assert np.array_equal(pix, got.astype(np.int64).sum(axis=3))
+
+
 @pytest.mark.parametrize("kernel", [0, 1])
 def test_without_affine_and_two_calls_in_a_row(kernel):
     """NULL scale/shift mean 1 and 0; a second call into the same buffers must
