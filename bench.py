@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per dsq_conv2d launch on this workload from two rocprofv3 --pmc runs
 # (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors from a 256 MiB copy kernel;
 # profiles/traffic_cfg2.md).  Algorithmic bytes are 7.55 MB.
-MEASURED_CONV_TRAFFIC_BYTES = {2: 9954681}
+MEASURED_CONV_TRAFFIC_BYTES = {2: 9954687}
 
 
 def parse_args():
