@@ -188,8 +188,24 @@ __device__ __forceinline__ int dsq_requant_store32(const DsqConvArgs &a, int m, 
     return total;
 }
 
-// One whole 32-channel tile of one pixel through the general formulas (any
-// l_a, any border).  All 64 lanes must call it.
+// Four consecutive channels o0..o0+3 of one pixel through the general formulas
+// (any l_a, any border): accumulators -> fp32 results -> the next layer's
+// codes, one per byte; adds the codes to `sum`.  o0 < Cop: the side tables cover it.
+__device__ __forceinline__ uint32_t dsq_requant_quarter(const DsqConvArgs &a, const DsqPixel &px, int o0, v4i acc,
+                                                        float delta_a, float delta_n, int top_n, int &sum)
+{
+    float y[4], sc[4], sh[4];
+    dsq_out4(a, px, o0, acc, delta_a, y);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const bool in = o0 + j < a.C_out;
+        sc[j] = in && a.rq_scale ? a.rq_scale[o0 + j] : 1.0f;
+        sh[j] = in && a.rq_shift ? a.rq_shift[o0 + j] : 0.0f;
+    }
+    return dsq_requant4(a, o0, y, sc, sh, delta_n, top_n, sum);
+}
+
+// One whole 32-channel tile of one pixel.  All 64 lanes must call it.
 __device__ __forceinline__ int dsq_requant_tile(const DsqConvArgs &a, const DsqPixel &px, int m, int o_tile,
                                                 int h, const v16i &acc, float delta_a)
 {
@@ -198,17 +214,9 @@ __device__ __forceinline__ int dsq_requant_tile(const DsqConvArgs &a, const DsqP
     uint32_t bytes[4];
     int sum = 0;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const int o0 = o_tile + 8 * q + 4 * h;            // < Cop: the side tables cover it
-        float y[4], sc[4], sh[4];
-        dsq_out4(a, px, o0, (v4i){acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]}, delta_a, y);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const bool in = o0 + j < a.C_out;
-            sc[j] = in && a.rq_scale ? a.rq_scale[o0 + j] : 1.0f;
-            sh[j] = in && a.rq_shift ? a.rq_shift[o0 + j] : 0.0f;
-        }
-        bytes[q] = dsq_requant4(a, o0, y, sc, sh, delta_n, top_n, sum);
-    }
+    for (int q = 0; q < 4; ++q)
+        bytes[q] = dsq_requant_quarter(a, px, o_tile + 8 * q + 4 * h,
+                                       (v4i){acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]}, delta_a,
+                                       delta_n, top_n, sum);
     return dsq_requant_store32(a, px.valid ? m : -1, o_tile, h, bytes, sum);
 }

@@ -12,7 +12,8 @@
 // rows and are turned into the matrix instruction's lane order through a
 // wave-private LDS area), the eight partial tiles are
 // added through LDS (integer adds: exact in any order), and four of the waves
-// run the shared dequantizing epilogue on a quarter of the tile each.  The
+// run the shared dequantizing epilogue (or, in chained mode, the next layer's
+// quantizer) on a quarter of the tile each.  The
 // packed formats are those of the other kernels (activations as written by
 // dsq_quantize_act, weights in matrix-instruction lane order), and so is the
 // arithmetic: int8 matrix instruction for 3/4-bit layers, the FP4 form for
@@ -35,7 +36,8 @@ struct FcLayout {
     static constexpr int WAVE_BYTES = 32 * ROW;
     static constexpr int STAGE_BYTES = FC_WAVES * WAVE_BYTES;
     static constexpr int PART_BYTES = FC_WAVES * 4 * 64 * 16;
-    static constexpr int LDS_BYTES = STAGE_BYTES > PART_BYTES ? STAGE_BYTES : PART_BYTES;
+    static constexpr int EXCH_BYTES = 2 * 4 * 64 * 4;         // chained mode: packed codes and code sums of four waves
+    static constexpr int LDS_BYTES = STAGE_BYTES > PART_BYTES + EXCH_BYTES ? STAGE_BYTES : PART_BYTES + EXCH_BYTES;
 };
 
 template <int CONT>
@@ -128,22 +130,36 @@ __global__ __launch_bounds__(64 * FC_WAVES) void conv_fc_kernel(DsqConvArgs a)
         part[(wave * 4 + q) * 64 + lane] = (v4i){acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
     __syncthreads();
     if (a.rq) {
-        // chained mode: one wave needs the whole tile (a lane pair holds whole
-        // packed words of its pixel); the next layer's codes and pixel sums
+        // chained mode: four waves turn a quarter of the tile each into the next
+        // layer's codes; a lane pair of one wave then needs all four quarters
+        // (it holds whole packed words of its pixel), so they meet in LDS and
+        // wave 0 packs, stores and adds to the pixel sums
+        uint32_t *exch = reinterpret_cast<uint32_t *>(lds + Lay::PART_BYTES);   // [codes | sums][quarter][lane]
+        const DsqPixel px = dsq_pixel_info(a, m, M);
+        if (wave < 4) {
+            const int q = wave;
+            v4i sum = part[q * 64 + lane];
+#pragma unroll
+            for (int w = 1; w < FC_WAVES; ++w) {
+                const v4i t = part[(w * 4 + q) * 64 + lane];
+                sum.x += t.x; sum.y += t.y; sum.z += t.z; sum.w += t.w;
+            }
+            const int top_n = (1 << a.rq_bits) - 1;
+            int codes = 0;
+            exch[q * 64 + lane] = dsq_requant_quarter(a, px, ct * 32 + 8 * q + 4 * h, sum, a.delta_a,
+                                                      dsq_delta(a.rq_l, a.rq_u, top_n), top_n, codes);
+            exch[(4 + q) * 64 + lane] = (uint32_t)codes;
+        }
+        __syncthreads();
         if (wave == 0) {
-            v16i tot;
+            uint32_t bytes[4];
+            int codes = 0;
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                v4i sum = part[q * 64 + lane];
-#pragma unroll
-                for (int w = 1; w < FC_WAVES; ++w) {
-                    const v4i t = part[(w * 4 + q) * 64 + lane];
-                    sum.x += t.x; sum.y += t.y; sum.z += t.z; sum.w += t.w;
-                }
-                tot[4 * q] = sum.x; tot[4 * q + 1] = sum.y; tot[4 * q + 2] = sum.z; tot[4 * q + 3] = sum.w;
+                bytes[q] = exch[q * 64 + lane];
+                codes += (int)exch[(4 + q) * 64 + lane];
             }
-            const DsqPixel px = dsq_pixel_info(a, m, M);
-            const int total = dsq_requant_tile(a, px, m, ct * 32, h, tot, a.delta_a);
+            const int total = dsq_requant_store32(a, px.valid ? m : -1, ct * 32, h, bytes, codes);
             if (h == 0 && px.valid) atomicAdd(a.rq_pix + m, total);
         }
         return;

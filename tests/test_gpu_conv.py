@@ -226,19 +226,16 @@ def test_binary_layer_is_the_convolution_of_signs(kernel):
     assert np.array_equal(got["out"].astype(np.float64), want)
 
 
-@pytest.mark.parametrize("kernel", [0, 1, 3])
-@pytest.mark.parametrize("bits_a,bits_w", [(4, 3), (3, 4), (2, 1), (1, 2), (4, 2), (4, 1), (3, 2), (3, 1)])
-def test_mixed_widths(bits_a, bits_w, kernel):
-    """Weights and activations of different widths: dsq_pack_weights_for is given
-    both, dsq_quantize_act and the layer descriptor the activations'."""
-    layer, inp = inputs.small_random_case(31, 2, 128, 7, 6, 72, 3, 1, 1, bits_a, l_a=0.0, u_a=2.2)
+def _check_mixed_widths(bits_a, bits_w, kernel, geom):
+    N, Ci, H, W, Co, R, stride, pad = geom
+    layer, inp = inputs.small_random_case(31, N, Ci, H, W, Co, R, stride, pad, bits_a, l_a=0.0, u_a=2.2)
     L = layer
-    buf = B.alloc_layer(L.N, L.C_in, L.H, L.W, L.C_out, 3, 3, 1, 1, bits_a, with_acc=True)
+    buf = B.alloc_layer(L.N, L.C_in, L.H, L.W, L.C_out, R, R, stride, pad, bits_a, with_acc=True)
     xd = inp["x"].permute(0, 2, 3, 1).contiguous().cuda()
     B.dsq_quantize_act(xd, B.DSQ_NHWC, L.N, L.C_in, L.H, L.W, inp["l_a"], inp["u_a"], bits_a,
                        buf.act_packed, buf.pix_code_sum)
     B.dsq_pack_weights_for(inp["w"].contiguous().cuda(), torch.from_numpy(inp["l_w"]).cuda(),
-                           torch.from_numpy(inp["u_w"]).cuda(), None, L.C_out, L.C_in, 3, 3, bits_w, bits_a,
+                           torch.from_numpy(inp["u_w"]).cuda(), None, L.C_out, L.C_in, R, R, bits_w, bits_a,
                            buf.w_packed, buf.w_aux)
     prev = B.dsq_set_conv_kernel(kernel)
     try:
@@ -249,14 +246,27 @@ def test_mixed_widths(bits_a, bits_w, kernel):
     torch.cuda.synchronize()
     a_code = oracle.quantize(inp["x"].numpy(), inp["l_a"], inp["u_a"], bits_a)
     w_code = oracle.quantize_weights(inp["w"].numpy(), inp["l_w"], inp["u_w"], bits_w)
-    assert np.array_equal(buf.acc.cpu().numpy().transpose(0, 3, 1, 2), oracle.conv_codes(a_code, w_code, 1, 1))
+    assert np.array_equal(buf.acc.cpu().numpy().transpose(0, 3, 1, 2), oracle.conv_codes(a_code, w_code, stride, pad))
     # the real-valued reference: dequantize each side with its own width
     a_hat = oracle.dequantize(a_code, inp["l_a"], inp["u_a"], bits_a)
     w_hat = np.stack([oracle.dequantize(w_code[o], float(inp["l_w"][o]), float(inp["u_w"][o]), bits_w)
                       for o in range(L.C_out)])
-    ref = oracle.conv_dequantized(a_hat, w_hat, 1, 1)
+    ref = oracle.conv_dequantized(a_hat, w_hat, stride, pad)
     dw = [oracle.delta(float(a), float(b), bits_w) for a, b in zip(inp["l_w"], inp["u_w"])]
     assert_out_close(buf.out.cpu().numpy().transpose(0, 3, 1, 2), ref, oracle.delta(inp["l_a"], inp["u_a"], bits_a), dw)
+
+
+@pytest.mark.parametrize("kernel", [0, 1, 3])
+@pytest.mark.parametrize("bits_a,bits_w", [(4, 3), (3, 4), (2, 1), (1, 2), (4, 2), (4, 1), (3, 2), (3, 1)])
+def test_mixed_widths(bits_a, bits_w, kernel):
+    """Weights and activations of different widths: dsq_pack_weights_for is given
+    both, dsq_quantize_act and the layer descriptor the activations'."""
+    _check_mixed_widths(bits_a, bits_w, kernel, (2, 128, 7, 6, 72, 3, 1, 1))
+
+
+@pytest.mark.parametrize("bits_a,bits_w", [(4, 3), (3, 4), (2, 1), (1, 2), (4, 1), (3, 2)])
+def test_mixed_widths_through_the_split_k_kernel(bits_a, bits_w):
+    _check_mixed_widths(bits_a, bits_w, 7, (37, 576, 1, 1, 40, 1, 1, 0))
 
 
 @pytest.mark.parametrize("kernel", [0, 1])
