@@ -200,7 +200,7 @@ dsq_status launch_conv(const DsqConvArgs &a, hipStream_t stream)
 {
     hipError_t e;
     if (g_conv_kernel == 7 || g_conv_kernel == 0) {
-        const bool fc_ok = dsq_conv_fc_supported(a);
+        const bool fc_ok = g_conv_kernel == 7 ? dsq_conv_fc_supported(a) : dsq_conv_fc_preferred(a);
         if (g_conv_kernel == 7 && !fc_ok) return DSQ_ERR_UNSUPPORTED;
         if (fc_ok) {
             e = dsq_launch_conv_fc(a, stream);

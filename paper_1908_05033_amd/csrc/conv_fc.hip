@@ -195,14 +195,26 @@ hipError_t launch_fc(const DsqConvArgs &a, hipStream_t stream)
 
 }  // namespace
 
-// 1x1, stride 1, no padding; few enough 32x32 tiles that splitting K inside the
-// workgroup pays, and K deep enough to split.
+// What the kernel takes: 1x1, stride 1, no padding, K deep enough to split among
+// eight waves, a bounded number of 32x32 tiles.
 bool dsq_conv_fc_supported(const DsqConvArgs &a)
 {
     if (a.R != 1 || a.stride != 1 || a.pad != 0) return false;
     const long long M = (long long)a.N * a.Ho * a.Wo;
     const long long tiles = ((M + 31) / 32) * ((a.C_out + 31) / 32);
     return a.Cp >= 512 && tiles <= 2048;
+}
+
+// Where it is also the faster kernel (measured against the implicit-GEMM kernels
+// on 1x1 layers of 49..12544 pixels and 512..4096 input channels): up to about
+// 800 tiles, or 1536 when the dot product is at least 2048 deep; past that the
+// per-tile cost of adding the partial tiles outweighs the idle compute units.
+bool dsq_conv_fc_preferred(const DsqConvArgs &a)
+{
+    if (!dsq_conv_fc_supported(a)) return false;
+    const long long M = (long long)a.N * a.Ho * a.Wo;
+    const long long tiles = ((M + 31) / 32) * ((a.C_out + 31) / 32);
+    return tiles <= 800 || (a.Cp >= 2048 && tiles <= 1536);
 }
 
 hipError_t dsq_launch_conv_fc(const DsqConvArgs &a, hipStream_t stream)

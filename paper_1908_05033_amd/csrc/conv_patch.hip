@@ -801,8 +801,9 @@ int pick_tile(const DsqConvArgs &a)
     // otherwise the 128x64 tile
     const int c_pad = ((a.C_out + 127) / 128) * 128;
     // (a 1x1 layer with at most 64 input channels is one matrix instruction deep:
-    // wasted channels cost nothing there, fewer and wider output tiles still pay)
-    const int waste_limit = (a.R == 1 && a.Cp <= 64) ? 2 : 4;
+    // wasted channels cost nothing there, fewer and wider output tiles still pay;
+    // not in chained mode, whose epilogue quantizes the wasted channels too)
+    const int waste_limit = (a.R == 1 && a.Cp <= 64 && !a.rq) ? 2 : 4;
     if (a.C_out > 64 && waste_limit * (c_pad - a.C_out) <= c_pad && blocks(kMedium) >= (a.R == 1 ? 320 : 192)) {
         // 2-bit layers (FP4 path: the 256x128 tile fits its registers): take that
         // tile when the 128x128 one leaves a nearly empty last round of workgroups

@@ -90,5 +90,6 @@ hipError_t dsq_launch_conv_patch(const DsqConvArgs &a, int force_tile, hipStream
 bool dsq_conv_patch_supported(const DsqConvArgs &a, int force_tile);
 
 // Split-K kernel for 1x1 layers with few output pixels (fully connected layers).
-bool dsq_conv_fc_supported(const DsqConvArgs &a);
+bool dsq_conv_fc_supported(const DsqConvArgs &a);   // the kernel takes this layer
+bool dsq_conv_fc_preferred(const DsqConvArgs &a);   // ... and is the faster choice for it
 hipError_t dsq_launch_conv_fc(const DsqConvArgs &a, hipStream_t stream);

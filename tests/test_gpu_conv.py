@@ -371,6 +371,7 @@ FC_SHAPES = [  # N, C_in, H, W, C_out : 1x1 layers with few pixels and a deep do
     (33, 2304, 1, 1, 128),
     (100, 640, 1, 1, 45),          # two pixel fragments per workgroup, the second one ragged
     (3, 576, 5, 9, 64),            # 135 pixels
+    (1, 512, 40, 40, 544),         # 850 tiles: the split-K kernel takes it when forced, not by itself
 ]
 
 
