@@ -8,7 +8,8 @@ dsq_pack_weights runs once per layer when a model is loaded; it is timed
 separately and is not part of the step.  The workload is the 3x3, 256->256,
 14x14, batch-32, 4-bit layer (the ResNet stage-3 shape).  Inputs live in HBM
 before the timed region; the steps rotate over enough buffer sets that the
-working set exceeds the 256 MB last-level cache.  By default the steps are dealt
+working set exceeds twice the 256 MB last-level cache (their number is chosen so
+that whole passes over them make exactly --steps steps).  By default the steps are dealt
 to four chains (four batches in flight, each running its own quantize -> conv
 in order), one hipGraph and one stream per chain, which is how a server with
 several requests in flight drives the library; --serial runs them strictly one
@@ -54,6 +55,24 @@ def parse_args():
     return ap.parse_args()
 
 
+def choose_sets(per_set, args):
+    """Number of buffer sets: the working set must exceed twice the 256 MB
+    last-level cache, a pass over the sets must deal every chain the same number
+    of steps, and whole passes should make up exactly --steps (and --warmup)
+    steps; the smallest such count is taken.  If none fits, the smallest count
+    of the right size is used and the step counts are rounded up to whole passes
+    (the JSON line reports what was run)."""
+    chains = 1 if args.serial else (args.streams if args.streams > 0 else 2)
+    lo = max(2, -(-520000000 // per_set))
+    lo = -(-lo // chains) * chains
+    cands = range(lo, 4 * lo + 1, chains)
+    for ok in (lambda n: args.steps % n == 0 and args.warmup % n == 0, lambda n: args.steps % n == 0):
+        fit = [n for n in cands if ok(n)]
+        if fit:
+            return fit[0]
+    return lo
+
+
 def main():
     args = parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -83,8 +102,7 @@ def main():
     out_bytes = L.N * L.Ho * L.Wo * L.C_out * 4
     code_bytes = B.dsq_act_packed_bytes(L.N, L.H, L.W, L.C_in, L.bits)
     per_set = in_bytes + out_bytes + code_bytes + L.N * L.H * L.W * 4
-    sets = args.sets or max(2, int(np.ceil(600e6 / per_set)))
-    sets = min(sets, 256)
+    sets = min(args.sets or choose_sets(per_set, args), 256)
 
     x_nhwc = inp["x"].permute(0, 2, 3, 1).contiguous()
     bufs = []
