@@ -61,11 +61,16 @@ def choose_sets(per_set, args):
     of steps, and whole passes should make up exactly --steps (and --warmup)
     steps; the smallest such count is taken.  If none fits, the smallest count
     of the right size is used and the step counts are rounded up to whole passes
-    (the JSON line reports what was run)."""
+    (the JSON line reports what was run).  At most 256 sets."""
     chains = 1 if args.serial else (args.streams if args.streams > 0 else 2)
     lo = max(2, -(-520000000 // per_set))
     lo = -(-lo // chains) * chains
-    cands = range(lo, 4 * lo + 1, chains)
+    cap = 256                     # (a tiny layer would need thousands of sets: the largest count that fits)
+    if lo > cap:
+        lo = cap - cap % chains
+        cands = range(lo, 0, -chains)
+    else:
+        cands = range(lo, min(4 * lo, cap) + 1, chains)
     for ok in (lambda n: args.steps % n == 0 and args.warmup % n == 0, lambda n: args.steps % n == 0):
         fit = [n for n in cands if ok(n)]
         if fit:
@@ -102,7 +107,7 @@ def main():
     out_bytes = L.N * L.Ho * L.Wo * L.C_out * 4
     code_bytes = B.dsq_act_packed_bytes(L.N, L.H, L.W, L.C_in, L.bits)
     per_set = in_bytes + out_bytes + code_bytes + L.N * L.H * L.W * 4
-    sets = min(args.sets or choose_sets(per_set, args), 256)
+    sets = min(args.sets or choose_sets(per_set, args), 256)   # (same cap as in choose_sets)
 
     x_nhwc = inp["x"].permute(0, 2, 3, 1).contiguous()
     bufs = []
