@@ -147,7 +147,7 @@ dsq_status conv_args(const dsq_conv_desc *d, const void *act_packed, const int32
     a.sw_tap = a.sw_total + Cop;
     a.out = nullptr; a.acc = nullptr; a.out_nchw = 0;
     a.rq = 0; a.rq_scale = nullptr; a.rq_shift = nullptr; a.rq_relu = 0;
-    a.rq_l = 0.f; a.rq_u = 1.f; a.rq_bits = 4; a.rq_Cp = 0; a.rq_codes = nullptr; a.rq_pix = nullptr;
+    a.rq_l = 0.f; a.rq_u = 1.f; a.rq_bits = 4; a.rq_Cp = 0; a.rq_codes = nullptr; a.rq_pix = nullptr; a.rq_store = 0;
     for (int j = 0; j < 16; ++j) a.rq_thr[j] = 0.f;
     a.rq_inv_delta = 0.f; a.rq_bias = 0.f;
     return DSQ_OK;
@@ -196,6 +196,15 @@ void quantizer_thresholds(float l, float u, int bits, float thr[16])
     }
 }
 
+// Chained mode: the kernels add every workgroup's share of a pixel's code sum
+// to the next layer's sums, which therefore start at zero (a fill kernel, not a
+// memset: callers may be capturing a graph).
+bool clear_next_sums(const DsqConvArgs &a, hipStream_t stream)
+{
+    if (!a.rq) return true;
+    return dsq_launch_fill_zero(a.rq_pix, (size_t)a.N * a.Ho * a.Wo, stream) == hipSuccess;
+}
+
 dsq_status launch_conv(const DsqConvArgs &a, hipStream_t stream)
 {
     hipError_t e;
@@ -203,6 +212,7 @@ dsq_status launch_conv(const DsqConvArgs &a, hipStream_t stream)
         const bool fc_ok = g_conv_kernel == 7 ? dsq_conv_fc_supported(a) : dsq_conv_fc_preferred(a);
         if (g_conv_kernel == 7 && !fc_ok) return DSQ_ERR_UNSUPPORTED;
         if (fc_ok) {
+            if (!clear_next_sums(a, stream)) return DSQ_ERR_HIP;
             e = dsq_launch_conv_fc(a, stream);
             return e == hipSuccess ? DSQ_OK : DSQ_ERR_HIP;
         }
@@ -210,8 +220,12 @@ dsq_status launch_conv(const DsqConvArgs &a, hipStream_t stream)
     const int force_tile = g_conv_kernel >= 3 ? g_conv_kernel - 3 : -1;
     const bool patch_ok = g_conv_kernel != 1 && dsq_conv_patch_supported(a, force_tile);
     if (g_conv_kernel >= 2 && !patch_ok) return DSQ_ERR_UNSUPPORTED;
-    if (!patch_ok) e = dsq_launch_conv_simple(a, stream);
-    else e = dsq_launch_conv_patch(a, force_tile, stream);
+    if (!patch_ok) {
+        if (!clear_next_sums(a, stream)) return DSQ_ERR_HIP;
+        e = dsq_launch_conv_simple(a, stream);
+    } else {
+        e = dsq_launch_conv_patch(a, force_tile, stream);     // (clears them itself where it adds to them)
+    }
     return e == hipSuccess ? DSQ_OK : DSQ_ERR_HIP;
 }
 
@@ -258,9 +272,6 @@ dsq_status dsq_conv2d_requant(const dsq_conv_desc *d, const void *act_packed,
         a.rq_inv_delta = 1.0f / delta_n;
         a.rq_bias = 0.5f;
     }
-    if (dsq_launch_fill_zero(pix_code_sum_next, (size_t)a.N * a.Ho * a.Wo, (hipStream_t)hip_stream) !=
-        hipSuccess)
-        return DSQ_ERR_HIP;
     return launch_conv(a, (hipStream_t)hip_stream);
 }
 

@@ -578,11 +578,15 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
         };
         if (top_n <= 3) chained(std::true_type{});
         else chained(std::false_type{});
-        // one integer atomic per pixel and wave (exact in any order)
+        // one integer atomic per pixel and wave (exact in any order); a plain
+        // store where this wave holds all channels of the layer
         if (h == 0) {
 #pragma unroll
-            for (int f = 0; f < PF; ++f)
-                if (frag_m[f] >= 0) atomicAdd(a.rq_pix + frag_m[f], psum[f]);
+            for (int f = 0; f < PF; ++f) {
+                if (frag_m[f] < 0) continue;
+                if (a.rq_store) a.rq_pix[frag_m[f]] = psum[f];
+                else atomicAdd(a.rq_pix + frag_m[f], psum[f]);
+            }
         }
     } else if (fast) {
         if (h == 0) {
@@ -864,11 +868,23 @@ bool dsq_conv_patch_supported(const DsqConvArgs &a, int force_tile)
     return choose_plan(a, force_tile, which, ks, pl);
 }
 
-hipError_t dsq_launch_conv_patch(const DsqConvArgs &a, int force_tile, hipStream_t stream)
+hipError_t dsq_launch_conv_patch(const DsqConvArgs &args, int force_tile, hipStream_t stream)
 {
     int which, ks;
     PatchPlan pl;
-    if (!choose_plan(a, force_tile, which, ks, pl)) return hipErrorInvalidValue;
+    if (!choose_plan(args, force_tile, which, ks, pl)) return hipErrorInvalidValue;
+    DsqConvArgs a = args;
+    if (a.rq) {
+        // Next layer's pixel sums: with one wave column, one wave group and a layer
+        // no wider than the tile, each pixel's sum is complete in one wave and is
+        // stored; otherwise the waves add to sums that a fill kernel clears first.
+        const TileCfg &tc = tile_cfg(which);
+        a.rq_store = tc.WC == 1 && ks == 1 && a.C_out <= 32 * tc.CT;
+        if (!a.rq_store) {
+            const hipError_t e = dsq_launch_fill_zero(a.rq_pix, (size_t)a.N * a.Ho * a.Wo, stream);
+            if (e != hipSuccess) return e;
+        }
+    }
     const int cont = dsq_container(a.bits);
     const int need = (pl.units + 255) / 256;      // fetch units per thread: instantiated 2, 4, 8, 12
 #define DSQ_TILE(CONT, RR, UPT)                                                                \

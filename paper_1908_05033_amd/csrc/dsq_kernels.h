@@ -43,7 +43,9 @@ struct DsqConvArgs {
     float rq_inv_delta, rq_bias;
     int rq_Cp;                // C_out rounded up to 64
     void *rq_codes;           // packed codes of the next layer's input
-    int32_t *rq_pix;          // [N*Ho*Wo], cleared before the launch
+    int32_t *rq_pix;          // [N*Ho*Wo]; the kernels add to it (cleared before the launch) unless rq_store
+    int rq_store;             // set by a launcher whose waves each hold all channels of their pixels:
+                              // plain stores to rq_pix, nothing to clear
 };
 
 // The quantizer of one tensor as a step function (see dsq_code_thr): thr[j],
