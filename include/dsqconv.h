@@ -211,8 +211,9 @@ dsq_status dsq_conv2d(const dsq_conv_desc *d, const void *act_packed,
  * pix_code_sum_next device, out, int32[N*Ho*Wo]; the call clears it with a fill
  *                   kernel on the same stream (no memset node, so the call can
  *                   be captured into a HIP graph) and accumulates with integer
- *                   atomics, which are exact in any order (narrow layers whose
- *                   sums are complete within one wave are stored directly)
+ *                   atomics, which are exact in any order (layers narrow enough
+ *                   that a pixel's sum is complete within one workgroup have
+ *                   it stored directly)
  */
 dsq_status dsq_conv2d_requant(const dsq_conv_desc *d, const void *act_packed,
                               const int32_t *pix_code_sum, float l_a, float u_a,

@@ -147,7 +147,7 @@ dsq_status conv_args(const dsq_conv_desc *d, const void *act_packed, const int32
     a.sw_tap = a.sw_total + Cop;
     a.out = nullptr; a.acc = nullptr; a.out_nchw = 0;
     a.rq = 0; a.rq_scale = nullptr; a.rq_shift = nullptr; a.rq_relu = 0;
-    a.rq_l = 0.f; a.rq_u = 1.f; a.rq_bits = 4; a.rq_Cp = 0; a.rq_codes = nullptr; a.rq_pix = nullptr; a.rq_store = 0;
+    a.rq_l = 0.f; a.rq_u = 1.f; a.rq_bits = 4; a.rq_Cp = 0; a.rq_codes = nullptr; a.rq_pix = nullptr; a.rq_store = 0; a.rq_share = 0;
     for (int j = 0; j < 16; ++j) a.rq_thr[j] = 0.f;
     a.rq_inv_delta = 0.f; a.rq_bias = 0.f;
     return DSQ_OK;

@@ -578,9 +578,35 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
         };
         if (top_n <= 3) chained(std::true_type{});
         else chained(std::false_type{});
-        // one integer atomic per pixel and wave (exact in any order); a plain
-        // store where this wave holds all channels of the layer
-        if (h == 0) {
+        // The waves that share a row of pixel fragments (wave columns, wave groups)
+        // hand their sums to the row's first wave through their staging slices
+        // (integer adds: exact in any order) ...
+        constexpr int SHARE = WC * KS;
+        const bool share = SHARE > 1 && a.rq_share;      // (uniform; otherwise every wave adds its own sums)
+        const bool first = !share || (wc == 0 && grp == 0);
+        if (share) {
+            if (!first && h == 0) {
+#pragma unroll
+                for (int f = 0; f < PF; ++f) m_stage[f * 32 + col] = psum[f];
+            }
+            lds_barrier();
+            if (first && h == 0) {
+#pragma unroll
+                for (int g = 0; g < KS; ++g)
+#pragma unroll
+                    for (int c2 = 0; c2 < WC; ++c2) {
+                        if (g == 0 && c2 == 0) continue;
+                        const int *theirs = reinterpret_cast<const int *>(lds + (g * 4 + wp + WP * c2) * EPI_WAVE + 32 * ROWB);
+#pragma unroll
+                        for (int f = 0; f < PF; ++f) psum[f] += theirs[f * 32 + col];
+                    }
+            }
+        }
+        // ... which adds them to the next layer's sums with one integer atomic per
+        // pixel, or stores them where the workgroup holds all channels of the layer.
+        // (The hand-over costs a barrier: measured, it pays where the sums can then
+        // be stored and on 1x1 layers, whose time is mostly epilogue.)
+        if (h == 0 && first) {
 #pragma unroll
             for (int f = 0; f < PF; ++f) {
                 if (frag_m[f] < 0) continue;
@@ -875,11 +901,12 @@ hipError_t dsq_launch_conv_patch(const DsqConvArgs &args, int force_tile, hipStr
     if (!choose_plan(args, force_tile, which, ks, pl)) return hipErrorInvalidValue;
     DsqConvArgs a = args;
     if (a.rq) {
-        // Next layer's pixel sums: with one wave column, one wave group and a layer
-        // no wider than the tile, each pixel's sum is complete in one wave and is
-        // stored; otherwise the waves add to sums that a fill kernel clears first.
+        // Next layer's pixel sums: a layer no wider than the tile has each pixel's
+        // sum complete in one workgroup, which stores it; otherwise the workgroups
+        // add to sums that a fill kernel clears first.
         const TileCfg &tc = tile_cfg(which);
-        a.rq_store = tc.WC == 1 && ks == 1 && a.C_out <= 32 * tc.CT;
+        a.rq_store = a.C_out <= 32 * tc.CT * tc.WC;
+        a.rq_share = a.rq_store || a.R == 1;
         if (!a.rq_store) {
             const hipError_t e = dsq_launch_fill_zero(a.rq_pix, (size_t)a.N * a.Ho * a.Wo, stream);
             if (e != hipSuccess) return e;

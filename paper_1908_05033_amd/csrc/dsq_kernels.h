@@ -44,8 +44,9 @@ struct DsqConvArgs {
     int rq_Cp;                // C_out rounded up to 64
     void *rq_codes;           // packed codes of the next layer's input
     int32_t *rq_pix;          // [N*Ho*Wo]; the kernels add to it (cleared before the launch) unless rq_store
-    int rq_store;             // set by a launcher whose waves each hold all channels of their pixels:
-                              // plain stores to rq_pix, nothing to clear
+    int rq_share;             // set by a launcher: the waves of a workgroup add up their pixel sums in LDS first
+    int rq_store;             // set by a launcher whose workgroups each hold all channels of their
+                              // pixels: plain stores to rq_pix, nothing to clear
 };
 
 // The quantizer of one tensor as a step function (see dsq_code_thr): thr[j],
