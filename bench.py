@@ -1,81 +1,82 @@
 #!/usr/bin/env python3
 """Benchmark of the b-bit quantized convolution hot path on one MI355X.
 
-A step is one pass of the per-batch hot path over one batch of synthetic
-input: dsq_quantize_act (fp32 activations -> packed codes + pixel sums)
-followed by dsq_conv2d (integer implicit GEMM + dequantizing epilogue -> fp32).
-dsq_pack_weights runs once per layer when a model is loaded; it is timed
-separately and is not part of the step.  The workload is the 3x3, 256->256,
-14x14, batch-32, 4-bit layer (the ResNet stage-3 shape).  Inputs live in HBM
-before the timed region; the steps rotate over enough buffer sets that the
-working set exceeds twice the 256 MB last-level cache (their number is chosen so
-that whole passes over them make exactly --steps steps).  By default the steps are dealt
-to four chains (four batches in flight, each running its own quantize -> conv
-in order), one hipGraph and one stream per chain, which is how a server with
-several requests in flight drives the library; --serial runs them strictly one
-after the other and is reported too.
+Workload (default): config 5, the VGG-16-shaped stack of twelve 3x3
+convolutions with C_in >= 64 at batch 32, 224x224 input, 2-bit activations and
+weights -- the largest of the five benchmark configs that fits one GPU
+(488 GMAC per step).  --config 3 runs the ResNet-18 stack (19 layers, batch 64,
+--bits 2/3/4), --config 4 the MobileNetV2 pointwise pairs.
 
-Prints ONE JSON line:  value = effective int-TOPS = 2*MACs*steps / time.
+A step is one pass of the whole hot path over one batch: for every layer of
+the stack, dsq_quantize_act (fp32 NHWC activations -> packed codes + pixel
+sums) followed by dsq_conv2d (integer implicit GEMM + dequantizing epilogue ->
+fp32).  The layers run strictly one after the other on one stream; the step is
+captured once as a hipGraph and replayed.  Every layer instance has buffers of
+its own (a step moves about 3 GB, far more than the 256 MB last-level cache),
+inputs are resident in HBM before the timed region, dsq_pack_weights ran once
+per layer at set-up (model-load time, not part of a step).  Activations and
+weights are synthetic tensors of the config's distributions drawn on the GPU
+with a seeded generator.
+
+Prints ONE JSON line:  value = effective int-TOPS = 2*MACs per step / step time.
+Besides the contract's keys it carries per-layer kernel times (each kernel
+timed by itself, events on its launch stream, rotating over more than 600 MB of
+buffer sets), the roofline of the kernel with the largest share of the step,
+the same stack through the chained call, the other configs as per-layer rows,
+and the CPU oracle timed on a batch subset of the same stack.
 """
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-INT8_MFMA_PEAK_TOPS = 5000.0     # MI355X dense int8 matrix peak
 HBM_PEAK_GBS = 8000.0
-
-# HBM bytes per dsq_conv2d launch on this workload from two rocprofv3 --pmc runs
-# (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors from a 256 MiB copy kernel;
-# profiles/traffic_cfg2.md).  Algorithmic bytes are 7.55 MB.
-MEASURED_CONV_TRAFFIC_BYTES = {2: 9954687}
 
 
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=2000)
-    ap.add_argument("--warmup", type=int, default=200)
-    ap.add_argument("--config", type=int, default=2, help="benchmark config (1 or 2)")
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=5, help="3 (ResNet-18 stack), 4 (MobileNetV2 pairs) or 5 (VGG-16 stack)")
+    ap.add_argument("--bits", type=int, default=None, help="code width for --config 3 (2, 3 or 4; default 4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--serial", action="store_true", help="no overlap between steps of different batches")
-    ap.add_argument("--sets", type=int, default=0, help="buffer sets to rotate over (0 = auto)")
-    ap.add_argument("--streams", type=int, default=4,
-                    help="run the steps as this many independent serial chains, one stream each "
-                         "(0 = the two-stream pipeline: quantize of batch i+1 beside conv of batch i)")
-    ap.add_argument("--latency-policy", action="store_true",
-                    help="keep the library's default kernel choice (shortest single call) although several "
-                         "steps are in flight; the default here is dsq_set_conv_policy(1)")
-    ap.add_argument("--one-graph", action="store_true",
-                    help="the chains as branches of a single graph instead of one graph per chain")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the chained-call step and the per-layer rows of the other configs")
+    ap.add_argument("--cpu-batch", type=int, default=0, help="images of the CPU-oracle sample (0 = auto)")
     return ap.parse_args()
 
 
-def choose_sets(per_set, args):
-    """Number of buffer sets: the working set must exceed twice the 256 MB
-    last-level cache, a pass over the sets must deal every chain the same number
-    of steps, and whole passes should make up exactly --steps (and --warmup)
-    steps; the smallest such count is taken.  If none fits, the smallest count
-    of the right size is used and the step counts are rounded up to whole passes
-    (the JSON line reports what was run).  At most 256 sets."""
-    chains = 1 if args.serial else (args.streams if args.streams > 0 else 2)
-    lo = max(2, -(-520000000 // per_set))
-    lo = -(-lo // chains) * chains
-    cap = 256                     # (a tiny layer would need thousands of sets: the largest count that fits)
-    if lo > cap:
-        lo = cap - cap % chains
-        cands = range(lo, 0, -chains)
-    else:
-        cands = range(lo, min(4 * lo, cap) + 1, chains)
-    for ok in (lambda n: args.steps % n == 0 and args.warmup % n == 0, lambda n: args.steps % n == 0):
-        fit = [n for n in cands if ok(n)]
-        if fit:
-            return fit[0]
-    return lo
+def workload_name(cfg, bits, layers):
+    what = {3: "ResNet-18 conv stack (19 convolutions after conv1), batch 64, 224x224 input",
+            4: "MobileNetV2 pointwise 1x1 pairs (5 layers), batch 64",
+            5: "VGG-16 3x3 conv stack (12 convolutions with C_in >= 64), batch 32, 224x224 input"}[cfg]
+    return "config %d: %s, %d-bit acts and weights" % (cfg, what, bits)
+
+
+def arithmetic_name(bits):
+    if bits <= 2:
+        return "u%d codes on the FP4 (e2m1) MFMA, f32 accumulate (exact integers), f64 epilogue -> f32" % bits
+    return "u%d codes on the int8 MFMA, int32 accumulate, f64 epilogue -> f32" % bits
+
+
+def tracked_traffic(layer_name):
+    """HBM bytes per launch of dsq_conv2d on this layer from the committed
+    rocprofv3 --pmc summary (FETCH_SIZE and WRITE_SIZE runs), or None."""
+    path = os.path.join(ROOT, "profiles", "traffic_conv.md")
+    if not os.path.exists(path):
+        return None, None
+    pat = re.compile(r"^\|\s*%s\s*\|.*?\|\s*(\d+)\s*\|\s*$" % re.escape(layer_name))
+    for line in open(path):
+        m = pat.match(line)
+        if m:
+            return int(m.group(1)), "profiles/traffic_conv.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a copy kernel)"
+    return None, None
 
 
 def main():
@@ -84,158 +85,63 @@ def main():
         print("bench.py: this build measures one GPU only (the path shards over the batch "
               "with no exchange step); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
+    if args.config not in (3, 4, 5):
+        print("bench.py: --config 3, 4 or 5 (configs 1 and 2 are single small layers; they are reported "
+              "as per-layer rows under other_workloads)", file=sys.stderr)
+        sys.exit(2)
+    if args.steps < 1 or args.warmup < 0:
+        print("bench.py: --steps >= 1, --warmup >= 0", file=sys.stderr)
+        sys.exit(2)
 
-    import numpy as np
     import torch
     from paper_1908_05033_amd import binding as B
     from paper_1908_05033_amd import inputs
+    from paper_1908_05033_amd import layer_bench as LB
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     B.load_library()
-    # several batches in flight: tell the library (it then spreads a layer differently);
-    # every figure of this run, the kernel durations included, is taken under the same policy
-    many_in_flight = not args.serial and not args.latency_policy
-    B.dsq_set_conv_policy(1 if many_in_flight else 0)
 
-    layer, inp = inputs.make_config_layer(args.config)
-    L = layer
-    macs = L.macs
+    layers = inputs.config_layers(args.config, args.bits)
+    bits = layers[0].bits
+    u_a = LB.HALF_NORMAL_Q[99.5 if args.config == 5 else 99.9]
+    gen = torch.Generator(device="cuda").manual_seed(inputs.BASE_SEED + 1000 * args.config)
 
-    # ---- buffers: one weight set, `sets` activation/output sets ------------
-    in_bytes = L.N * L.C_in * L.H * L.W * 4
-    out_bytes = L.N * L.Ho * L.Wo * L.C_out * 4
-    code_bytes = B.dsq_act_packed_bytes(L.N, L.H, L.W, L.C_in, L.bits)
-    per_set = in_bytes + out_bytes + code_bytes + L.N * L.H * L.W * 4
-    sets = min(args.sets or choose_sets(per_set, args), 256)   # (same cap as in choose_sets)
-
-    x_nhwc = inp["x"].permute(0, 2, 3, 1).contiguous()
-    bufs = []
-    for s in range(sets):
-        b = B.alloc_layer(L.N, L.C_in, L.H, L.W, L.C_out, L.R, L.S, L.stride, L.pad, L.bits)
-        b.x = x_nhwc.cuda() if s == 0 else bufs[0].x.clone()
-        bufs.append(b)
-    w = inp["w"].contiguous().cuda()
-    lw = torch.from_numpy(inp["l_w"]).cuda()
-    uw = torch.from_numpy(inp["u_w"]).cuda()
-    w_packed, w_aux = bufs[0].w_packed, bufs[0].w_aux
-    l_a, u_a = inp["l_a"], inp["u_a"]
+    # ---- buffers: per layer shape, one set per instance of the stack, and more
+    # sets where the per-kernel timing needs them to stay out of the cache ------
+    states = [LB.LayerState(L, max(L.count, LB.cold_sets(L)), chained=not args.no_extras, u_a=u_a, gen=gen)
+              for L in layers]
+    step_calls, chained_calls = [], []
+    for st in states:
+        for b in st.bufs[:st.L.count]:
+            step_calls += [lambda st=st, b=b: st.quant(b), lambda st=st, b=b: st.conv(b)]
+            if st.chained:
+                chained_calls.append(lambda st=st, b=b: st.conv_chained(b))
+    macs = sum(L.macs * L.count for L in layers)
+    n_inst = sum(L.count for L in layers)
 
     stream = torch.cuda.Stream()
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-
-    def pack():
-        B.dsq_pack_weights(w, lw, uw, None, L.C_out, L.C_in, L.R, L.S, L.bits, w_packed, w_aux)
-
-    def quant(b):
-        B.dsq_quantize_act(b.x, B.DSQ_NHWC, L.N, L.C_in, L.H, L.W, l_a, u_a, L.bits,
-                           b.act_packed, b.pix_code_sum)
-
-    def conv(b):
-        B.dsq_conv2d(b.desc, b.act_packed, b.pix_code_sum, l_a, u_a, w_packed, w_aux, b.out,
-                     B.DSQ_NHWC, None)
-
-    def capture(fn):
-        g = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(g, stream=stream):
-            for b in bufs:
-                fn(b)
-        return g
-
-    side = torch.cuda.Stream()
-
-    def capture_pipelined():
-        """All steps of one pass over the buffer sets, software-pipelined over two
-        streams the way a serving loop double-buffers batches: the activations of
-        batch i+1 are quantized (side stream) while batch i is convolved (launch
-        stream).  Every step still runs quantize then conv on its own batch; only
-        steps of different batches overlap."""
-        g = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(g, stream=stream):
-            ready = []
-            side.wait_stream(stream)
-            with torch.cuda.stream(side):
-                quant(bufs[0])
-                e = torch.cuda.Event()
-                e.record(side)
-                ready.append(e)
-            for i, b in enumerate(bufs):
-                if i + 1 < len(bufs):
-                    with torch.cuda.stream(side):
-                        quant(bufs[i + 1])
-                        e = torch.cuda.Event()
-                        e.record(side)
-                        ready.append(e)
-                stream.wait_event(ready[i])
-                conv(b)
-            stream.wait_stream(side)
-        return g
-
-    def capture_chains(n_chains):
-        """The steps dealt round-robin to n_chains streams; each stream runs its
-        steps (quantize then conv of one batch) strictly in order, the streams run
-        side by side, the way a server keeps several requests in flight."""
-        chains = [torch.cuda.Stream() for _ in range(n_chains)]
-        g = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(g, stream=stream):
-            for c, st in enumerate(chains):
-                st.wait_stream(stream)
-                with torch.cuda.stream(st):
-                    for b in bufs[c::n_chains]:
-                        quant(b)
-                        conv(b)
-            for st in chains:
-                stream.wait_stream(st)
-        return g
-
-    def capture_chain_graphs(n_chains):
-        """One graph per chain: the steps dealt round-robin to n_chains chains, each
-        captured as a strictly serial graph of its own."""
-        graphs = []
-        for c in range(n_chains):
-            g = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g, stream=stream):
-                for b in bufs[c::n_chains]:
-                    quant(b)
-                    conv(b)
-            graphs.append(g)
-        return graphs
-
-    def timed_chain_replays(graphs, streams, n):
-        """n replays of every chain graph, chain c on streams[c], between two events
-        on the launch stream (which the chain streams wait for and are joined to)."""
+    with torch.cuda.stream(stream):
+        for st in states:
+            for b in st.bufs:
+                st.quant(b)
+                st.conv(b)
+                if st.chained:
+                    st.conv_chained(b)
         torch.cuda.synchronize()
-        ev0.record(stream)
-        for st in streams:
-            st.wait_event(ev0)
-        for _ in range(n):
-            for g, st in zip(graphs, streams):
-                with torch.cuda.stream(st):
-                    g.replay()
-        for st in streams:
-            stream.wait_stream(st)
-        ev1.record(stream)
-        torch.cuda.synchronize()
-        return ev0.elapsed_time(ev1) * 1e-3
 
-    def pick_streams(graphs, n_chains):
-        """HIP multiplexes its streams onto a few hardware queues; chains whose
-        streams share a queue run one after the other.  Which streams share one is
-        not visible from here, so a short calibration run tries windows of
-        consecutive streams from a small pool and keeps the fastest."""
-        pool = [torch.cuda.Stream() for _ in range(n_chains + 6)]
-        best, best_t = None, None
-        for o in range(len(pool) - n_chains + 1):
-            cand = pool[o:o + n_chains]
-            timed_chain_replays(graphs, cand, 1)
-            t = min(timed_chain_replays(graphs, cand, 2) for _ in range(2))
-            if best_t is None or t < best_t:
-                best, best_t = cand, t
-        return best
+    def capture(calls):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=stream):
+            for fn in calls:
+                fn()
+        return g
 
-    def timed_replays(g, n):
-        """n replays of a graph between two events on the launch stream."""
+    def timed_replays(g, warm, n):
         with torch.cuda.stream(stream):
+            for _ in range(warm):
+                g.replay()
             torch.cuda.synchronize()
             ev0.record(stream)
             for _ in range(n):
@@ -244,147 +150,134 @@ def main():
             torch.cuda.synchronize()
         return ev0.elapsed_time(ev1) * 1e-3
 
-    with torch.cuda.stream(stream):
-        pack()
-        for b in bufs:
-            quant(b)
-            conv(b)
-        torch.cuda.synchronize()
-        # weight packing, timed on its own (model-load time, not part of a step)
-        ev0.record(stream)
-        for _ in range(10):
-            pack()
-        ev1.record(stream)
-        torch.cuda.synchronize()
-        pack_ms = ev0.elapsed_time(ev1) / 10
-
-    def step(b):
-        quant(b)
-        conv(b)
-
-    g_step, g_quant, g_conv = capture(step), capture(quant), capture(conv)
-    chain_graphs = chain_streams = None
-    if args.serial:
-        g_pipe = g_step
-    elif args.streams > 0 and not args.one_graph:
-        g_pipe = None
-        chain_graphs = capture_chain_graphs(args.streams)
-        chain_streams = pick_streams(chain_graphs, args.streams)
-    elif args.streams > 0:
-        g_pipe = capture_chains(args.streams)
-    else:
-        g_pipe = capture_pipelined()
-
-    def timed_pass(n):
-        if chain_graphs is not None:
-            return timed_chain_replays(chain_graphs, chain_streams, n)
-        return timed_replays(g_pipe, n)
-
-    # ---- the timed region: exactly `steps` steps ---------------------------
-    n_warm = max(1, -(-args.warmup // sets))
-    n_rep = max(1, -(-args.steps // sets))
-    steps = n_rep * sets
-    warmup = n_warm * sets
-    timed_pass(n_warm)
-    torch.cuda.synchronize()
+    # ---- the timed region: exactly --steps steps after --warmup steps --------
+    g_step = capture(step_calls)
     t0 = time.perf_counter()
-    gpu_s = timed_pass(n_rep)
+    gpu_s = timed_replays(g_step, args.warmup, args.steps)
     wall_s = time.perf_counter() - t0
-    step_s = max(gpu_s, 0.0) / steps
+    step_s = gpu_s / args.steps
     value = 2.0 * macs / step_s / 1e12
-    # the same steps strictly one after the other on one stream
-    timed_replays(g_step, n_warm)
-    serial_step_s = timed_replays(g_step, n_rep) / steps
 
-    # ---- per-kernel average launch durations, same stream, HIP events ------
-    timed_replays(g_conv, n_warm)
-    conv_s = timed_replays(g_conv, n_rep) / steps
-    timed_replays(g_quant, n_warm)
-    quant_s = timed_replays(g_quant, n_rep) / steps
+    # ---- per-kernel average launch durations (each kernel by itself) ---------
+    rows, share = [], []
+    for st in states:
+        L = st.L
+        reps = 3 if len(st.bufs) * LB.LayerState.bytes_per_set(L) > 1e9 else 6
+        tc = LB.time_graph(st.calls(st.conv), stream, reps)
+        tq = LB.time_graph(st.calls(st.quant), stream, reps)
+        ops = 2.0 * L.macs
+        peak = LB.matrix_peak_tops(L.bits)
+        bound = "mfma" if ops / st.conv_alg_bytes() >= peak * 1e12 / (HBM_PEAK_GBS * 1e9) else "hbm"
+        rows.append({
+            "layer": L.name, "count": L.count, "gemm_MxNxK": [L.N * L.Ho * L.Wo, L.C_out, L.C_in * L.R * L.S],
+            "conv_us": round(tc * 1e6, 2), "conv_TOPS": round(ops / tc / 1e12, 1),
+            "conv_frac_matrix_peak": round(ops / tc / 1e12 / peak, 4),
+            "conv_frac_int8_peak": round(ops / tc / 1e12 / LB.INT8_PEAK_TOPS, 4),
+            "conv_GBps": round(st.conv_alg_bytes() / tc / 1e9, 1), "bound": bound,
+            "quant_us": round(tq * 1e6, 2), "quant_GBps": round(st.quant_alg_bytes() / tq / 1e9, 1),
+        })
+        share.append((L.count * tc, st, tc, bound, peak))
+    share.sort(key=lambda t: -t[0])
+    _, dom, dom_t, dom_bound, dom_peak = share[0]
+    dom_ops, dom_bytes = 2.0 * dom.L.macs, dom.conv_alg_bytes()
+    traffic, traffic_source = tracked_traffic(dom.L.name)
+    if dom_bound == "mfma":
+        roofline = {"kernel": "dsq_conv2d on %s" % dom.L.name, "bound": "mfma",
+                    "achieved": round(dom_ops / dom_t / 1e12, 2), "peak": dom_peak, "unit": "TOP/s",
+                    "frac": round(dom_ops / dom_t / 1e12 / dom_peak, 4),
+                    "peak_is": "dense %s matrix peak" % ("FP4" if dom.L.bits <= 2 else "int8"),
+                    "algorithmic_ops_per_launch": int(dom_ops)}
+    else:
+        roofline = {"kernel": "dsq_conv2d on %s" % dom.L.name, "bound": "hbm",
+                    "achieved": round(dom_bytes / dom_t / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": round(dom_bytes / dom_t / 1e9 / HBM_PEAK_GBS, 4),
+                    "algorithmic_bytes_per_launch": int(dom_bytes)}
+    roofline.update({"traffic": traffic, "traffic_source": traffic_source,
+                     "launch_us": round(dom_t * 1e6, 2),
+                     "share_of_step": round(share[0][0] / step_s, 3)})
 
-    # the same kernel call under the other policy, for the record
-    B.dsq_set_conv_policy(0 if many_in_flight else 1)
-    g_conv_other = capture(conv)
-    B.dsq_set_conv_policy(1 if many_in_flight else 0)
-    timed_replays(g_conv_other, n_warm)
-    conv_other_s = timed_replays(g_conv_other, n_rep) / steps
-
-    conv_tops = 2.0 * macs / conv_s / 1e12
-    quant_bytes = in_bytes + code_bytes + L.N * L.H * L.W * 4
     result = {
         "metric": "effective int-TOPS of b-bit conv2d (2*MACs/s), 1 GPU",
-        "value": round(value, 3),
+        "value": round(value, 2),
         "unit": "TOPS",
         "n_gpus": 1,
-        "steps": steps,
-        "warmup": warmup,
-        "ms_per_step": round(step_s * 1e3, 6),
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(step_s * 1e3, 5),
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "u%d codes, int8 MFMA, int32 accumulate, f64 epilogue -> f32" % L.bits,
+        "dtype": arithmetic_name(bits),
         "data": "synthetic",
         "config": {
-            "workload": "config %d: %dx%d conv stride %d pad %d, N=%d, C_in=%d, C_out=%d, %dx%d, %d-bit "
-                        "acts and weights" % (args.config, L.R, L.S, L.stride, L.pad, L.N, L.C_in, L.C_out,
-                                              L.H, L.W, L.bits),
-            "step": "dsq_quantize_act + dsq_conv2d (weights packed once, outside the step)",
-            "gemm_MxNxK": [L.N * L.Ho * L.Wo, L.C_out, L.C_in * L.R * L.S],
+            "workload": workload_name(args.config, bits, layers),
+            "step": "for each of the %d layers: dsq_quantize_act + dsq_conv2d, strictly serial on one stream "
+                    "(one hipGraph per step; weights packed once, outside the step)" % n_inst,
             "macs_per_step": macs,
-            "buffer_sets": sets,
-            "kernel_policy": "dsq_set_conv_policy(1): several calls in flight" if many_in_flight else
-                             "dsq_set_conv_policy(0): shortest single call",
-            "launch": ("%d steps per pass, %d passes; " % (sets, n_rep)) +
-                      ("one hipGraph, steps strictly serial on one stream" if args.serial else
-                       "%d hipGraphs, each a serial chain of every %dth step, replayed side by side on %d streams "
-                       "(picked from a pool of %d by a calibration run: streams that share a hardware queue "
-                       "would serialise)" % (args.streams, args.streams, args.streams, args.streams + 6)
-                       if chain_graphs is not None else
-                       "one hipGraph with %d independent chains of serial steps as branches" % args.streams
-                       if args.streams > 0 else
-                       "one hipGraph, quantize of batch i+1 overlaps conv of batch i (two streams)"),
+            "launches_per_step": 2 * n_inst,
         },
-        "kernels": {
-            "serial_step_us": round(serial_step_s * 1e6, 3),
-            "dsq_conv2d_us": round(conv_s * 1e6, 3),
-            "dsq_conv2d_TOPS": round(conv_tops, 2),
-            "dsq_conv2d_us_under_policy_%d" % (0 if many_in_flight else 1): round(conv_other_s * 1e6, 3),
-            "dsq_quantize_act_us": round(quant_s * 1e6, 3),
-            "dsq_quantize_act_GBps": round(quant_bytes / quant_s / 1e9, 1),
-            "dsq_pack_weights_us_not_in_step": round(pack_ms * 1e3, 2),
-            "host_wall_s_timed_region": round(wall_s, 4),
-        },
-        "roofline": {
-            "kernel": "dsq_conv2d",
-            "bound": "mfma",
-            "achieved": round(conv_tops, 2),
-            "peak": INT8_MFMA_PEAK_TOPS,
-            "unit": "TOP/s",
-            "frac": round(conv_tops / INT8_MFMA_PEAK_TOPS, 4),
-            "traffic": MEASURED_CONV_TRAFFIC_BYTES.get(args.config),
-            "algorithmic_ops_per_launch": 2 * macs,
-        },
+        "frac_int8_mfma_peak": round(value / LB.INT8_PEAK_TOPS, 4),
+        "host_wall_s_timed_region": round(wall_s, 4),
+        "roofline": roofline,
+        "layers": rows,
     }
+
+    if not args.no_extras:
+        # the same stack through dsq_conv2d_requant (every layer writes the next layer's
+        # packed codes instead of fp32; no dsq_quantize_act between the layers)
+        g_ch = capture(chained_calls)
+        ch_s = timed_replays(g_ch, args.warmup, args.steps) / args.steps
+        result["chained_step"] = {"ms_per_step": round(ch_s * 1e3, 5), "TOPS": round(2.0 * macs / ch_s / 1e12, 2),
+                                  "step": "dsq_conv2d_requant per layer (codes in, codes out)"}
+        del g_ch
+    del g_step, step_calls, chained_calls, states, share, dom
+    torch.cuda.empty_cache()
+
+    if not args.no_extras:
+        other = {}
+        for cfg, b in ((3, 4), (2, None), (1, None)):
+            if cfg == args.config and (b is None or b == bits):
+                continue
+            lrows, tot_t, tot_macs = [], 0.0, 0
+            for L in inputs.config_layers(cfg, b):
+                r = LB.bench_layer(L, reps=3, u_a=LB.HALF_NORMAL_Q[99.9] if cfg >= 3 else (3.0 if cfg == 1 else 2.5))
+                lrows.append({k: r[k] for k in ("layer", "count", "conv_us", "conv_warm_us", "conv_TOPS",
+                                                "conv_frac_matrix_peak", "conv_GBps", "quant_us", "quant_warm_us",
+                                                "quant_GBps", "buffer_sets")})
+                tot_t += (r["conv_us"] + r["quant_us"]) * 1e-6 * L.count
+                tot_macs += L.macs * L.count
+                torch.cuda.empty_cache()
+            other["config%d%s" % (cfg, "_%dbit" % b if b else "")] = {
+                "quant_plus_conv_ms": round(tot_t * 1e3, 4), "TOPS": round(2.0 * tot_macs / tot_t / 1e12, 1),
+                "timing": "sum of per-kernel times, each kernel alone, buffer sets rotating over > 600 MB (cold)",
+                "layers": lrows}
+        result["other_workloads"] = other
 
     if not args.no_cpu_baseline:
         import oracle
-        xs = inp["x"].numpy()
-        ws = inp["w"].numpy()
-        w_code = oracle.quantize_weights(ws, inp["l_w"], inp["u_w"], L.bits)   # once per layer, like the GPU
-        t0 = time.perf_counter()
-        passes = 0
-        while passes < 64 and (passes == 0 or time.perf_counter() - t0 < 6.0):
-            a_code = oracle.quantize(xs, l_a, u_a, L.bits)
-            oracle.conv_real(a_code, l_a, u_a, w_code, inp["l_w"], inp["u_w"], L.bits, L.stride, L.pad)
-            passes += 1
-        cpu_s = (time.perf_counter() - t0) / passes
+        # the oracle as it stands on a batch subset of the same stack: quantize + direct
+        # convolution of the dequantized doubles, every layer; 2*MACs/s needs no scaling
+        n_sub = args.cpu_batch or {3: 8, 4: 64, 5: 2}[args.config]
+        cpu_t, cpu_macs = 0.0, 0
+        for li, L in enumerate(layers):
+            Ls, inp = inputs.make_config_layer(args.config, li, bits=args.bits, batch=n_sub)
+            xs, ws = inp["x"].numpy(), inp["w"].numpy()
+            w_code = oracle.quantize_weights(ws, inp["l_w"], inp["u_w"], Ls.bits)   # once per layer, like the GPU
+            t0 = time.perf_counter()
+            a_code = oracle.quantize(xs, inp["l_a"], inp["u_a"], Ls.bits)
+            oracle.conv_real(a_code, inp["l_a"], inp["u_a"], w_code, inp["l_w"], inp["u_w"], Ls.bits, Ls.stride, Ls.pad)
+            dt = time.perf_counter() - t0
+            cpu_t += dt * L.count
+            cpu_macs += Ls.macs * L.count
         result["cpu_baseline"] = {
-            "value": round(2.0 * macs / cpu_s / 1e12, 6),
+            "value": round(2.0 * cpu_macs / cpu_t / 1e12, 6),
             "unit": "TOPS",
             "cores": oracle.threads(),
             "kind": "oracle",
-            "sample": "%d passes over one full batch of the same workload (quantize + direct conv on "
-                      "dequantized doubles), %.3f s per pass, %.1f s in all" % (passes, cpu_s, cpu_s * passes),
+            "sample": "the same stack at batch %d instead of %d (every layer once, repeated shapes counted "
+                      "by their multiplicity): quantize + direct convolution of the dequantized doubles, "
+                      "%.1f s of CPU work for %.1f GMAC; a rate, so no scaling to the full batch is needed"
+                      % (n_sub, layers[0].N, cpu_t, cpu_macs / 1e9),
         }
     print(json.dumps(result))
 

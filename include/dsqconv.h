@@ -23,6 +23,8 @@
  *     returns at once.
  *   - Arguments are validated on the host before anything is launched; on any
  *     error nothing has been enqueued.  Errors are return codes only.
+ *   - The library holds no mutable state: every call is a function of its
+ *     arguments and may run concurrently with any other call.
  *   - Device pointers must be 16-byte aligned.
  *   - bits is 1, 2, 3 or 4.  The descriptor's bits is the activations' width; the
  *     weights may have another one (dsq_pack_weights_for; their step travels in
@@ -94,11 +96,40 @@ typedef enum {
 
 typedef enum { DSQ_NHWC = 0, DSQ_NCHW = 1 } dsq_layout;
 
+/* Per-call choices of the convolution entry points, OR-ed into
+ * dsq_conv_desc.flags.  0 is the normal value: the library picks the kernel
+ * and optimises for the shortest time of a single call on an otherwise idle
+ * GPU.  The library keeps no state between calls: everything a call depends
+ * on is in its arguments, so calls from several threads or streams do not
+ * interfere.
+ *
+ * DSQ_CONV_KERNEL(k), k = 0..7, selects the kernel (for tests and
+ *   benchmarking): 0 = automatic, 1 = the simple one-wave-per-tile kernel,
+ *   2 = the LDS-patch kernel with its tile chosen by problem size, 3 / 4 / 5 / 6
+ *   = the LDS-patch kernel with the 128x64 / 128x128 / 256x128 / 256x64
+ *   (pixels x channels) tile, 7 = the split-K kernel for 1x1 layers with few
+ *   output pixels and at least 512 input channels (fully connected layers;
+ *   taken automatically for those).  With 2..7 the call returns
+ *   DSQ_ERR_UNSUPPORTED instead of falling back when the chosen kernel cannot
+ *   take the geometry (the 256x128 tile has no dsq_conv2d_requant variant and
+ *   reports the same).
+ * DSQ_CONV_MANY_IN_FLIGHT tells the automatic choice that the caller keeps
+ *   several calls in flight on different streams (a server with several
+ *   requests, independent branches of a network): layers that yield only about
+ *   one workgroup per compute unit then run with one wave group per workgroup
+ *   instead of two, so that workgroups of different calls share the compute
+ *   units.  Results are identical bit for bit either way.
+ * Any other bit set gives DSQ_ERR_UNSUPPORTED.
+ */
+#define DSQ_CONV_KERNEL(k) ((k) & 15)
+#define DSQ_CONV_MANY_IN_FLIGHT 0x10
+
 typedef struct {
     int N, C_in, H, W;   /* input activation */
     int C_out, R, S;     /* filter bank (R = S) */
     int stride, pad;
     int bits;
+    int flags;           /* 0, or DSQ_CONV_* values OR-ed together */
 } dsq_conv_desc;
 
 /* ---- sizes (pure host functions; 0 on invalid arguments) ---------------- */
@@ -134,8 +165,9 @@ dsq_status dsq_quantize_act(const float *x, dsq_layout layout, int N, int C,
  *              not finite or not l<u gets delta_w = NaN, which makes that
  *              channel's outputs NaN; validate ranges on the host if needed.
  * codes_oihw   device, uint8 [C_out][C_in][R][S] or NULL.  If non-NULL the
- *              quantizer is skipped and these codes (must be < 2^bits) are
- *              packed as they are.
+ *              quantizer is skipped and these codes are packed as they are;
+ *              a code above 2^bits - 1 is stored as 2^bits - 1 (saturated, as
+ *              the quantizer saturates a value above u).
  * w_packed     device, out, dsq_wgt_packed_bytes() bytes
  * w_aux        device, out, dsq_wgt_aux_bytes() bytes
  */
@@ -252,30 +284,6 @@ dsq_status dsq_soft_quantize_bwd(const float *x, const float *grad_y, size_t n,
                                  float l, float u, float alpha, int bits,
                                  float *grad_x, double *grad_alpha_l_u,
                                  void *hip_stream);
-
-/* Selects the convolution kernel: 0 = automatic (default), 1 = the simple
- * one-wave-per-tile kernel, 2 = the LDS-patch kernel with its tile chosen by
- * problem size, 3 / 4 / 5 / 6 = the LDS-patch kernel with the 128x64 / 128x128 /
- * 256x128 / 256x64 (pixels x channels) tile, 7 = the split-K kernel for 1x1
- * layers with few output pixels and at least 512 input channels (fully
- * connected layers; taken automatically for those).  With 2..7, dsq_conv2d
- * returns DSQ_ERR_UNSUPPORTED instead of falling back when the chosen kernel
- * cannot take the geometry (the 256x128 tile has no dsq_conv2d_requant
- * variant and reports the same).  For tests and
- * benchmarking; this selector and the policy below are the only state the
- * library keeps; process-wide, not thread-safe.  Returns the previous value;
- * values outside 0..7 change nothing. */
-int dsq_set_conv_kernel(int which);
-
-/* What the automatic kernel choice optimises for.  0 (default): the shortest
- * time of a single call on an otherwise idle GPU -- layers that yield only
- * about one workgroup per compute unit run with two wave groups per workgroup.
- * 1: the highest throughput when the caller keeps several calls in flight on
- * different streams (a server with several requests, several layers of
- * independent branches) -- one wave group per workgroup, so that workgroups
- * of different calls share the compute units.  Results are identical either
- * way.  Returns the previous value; other values change nothing. */
-int dsq_set_conv_policy(int policy);
 
 /* Static, NUL-terminated description of a status code. */
 const char *dsq_status_string(dsq_status s);

@@ -17,12 +17,17 @@ LIB_PATH = os.path.join(HERE, "libdsqconv.so")
 
 DSQ_NHWC, DSQ_NCHW = 0, 1
 DSQ_OK = 0
+DSQ_CONV_MANY_IN_FLIGHT = 0x10
+
+
+def DSQ_CONV_KERNEL(k):
+    return k & 15
 
 EXPORTS = [
     "dsq_act_packed_bytes", "dsq_wgt_packed_bytes", "dsq_wgt_aux_bytes",
     "dsq_quantize_act", "dsq_pack_weights", "dsq_pack_weights_for", "dsq_conv2d", "dsq_conv2d_requant",
     "dsq_soft_quantize_fwd", "dsq_soft_quantize_bwd",
-    "dsq_set_conv_kernel", "dsq_set_conv_policy", "dsq_status_string",
+    "dsq_status_string",
 ]
 
 
@@ -34,7 +39,7 @@ class DsqError(RuntimeError):
 
 class dsq_conv_desc(C.Structure):
     _fields_ = [(n, C.c_int) for n in
-                ("N", "C_in", "H", "W", "C_out", "R", "S", "stride", "pad", "bits")]
+                ("N", "C_in", "H", "W", "C_out", "R", "S", "stride", "pad", "bits", "flags")]
 
 
 _lib = None
@@ -73,10 +78,6 @@ def load_library():
     lib.dsq_soft_quantize_fwd.argtypes = [vp, sz, f, f, f, i, vp, vp]
     lib.dsq_soft_quantize_bwd.restype = i
     lib.dsq_soft_quantize_bwd.argtypes = [vp, vp, sz, f, f, f, i, vp, vp, vp]
-    lib.dsq_set_conv_kernel.restype = i
-    lib.dsq_set_conv_kernel.argtypes = [i]
-    lib.dsq_set_conv_policy.restype = i
-    lib.dsq_set_conv_policy.argtypes = [i]
     lib.dsq_status_string.restype = C.c_char_p
     lib.dsq_status_string.argtypes = [i]
     _lib = lib
@@ -186,14 +187,6 @@ def dsq_soft_quantize_bwd(x, grad_y, l, u, alpha, bits, grad_x, grad_alpha_l_u, 
         _dev_ptr(grad_x, torch.float32), _dev_ptr(grad_alpha_l_u, torch.float64), _stream(stream)))
 
 
-def dsq_set_conv_kernel(which):
-    return int(load_library().dsq_set_conv_kernel(which))
-
-
-def dsq_set_conv_policy(policy):
-    return int(load_library().dsq_set_conv_policy(policy))
-
-
 # ---------------------------------------------------------------------------
 # Small conveniences: buffer allocation for one layer (still no arithmetic).
 # ---------------------------------------------------------------------------
@@ -209,17 +202,17 @@ class LayerBuffers:
     acc: torch.Tensor = None   # NHWC int32, optional
 
 
-def make_desc(N, C_in, H, W, C_out, R, S, stride, pad, bits):
-    return dsq_conv_desc(N, C_in, H, W, C_out, R, S, stride, pad, bits)
+def make_desc(N, C_in, H, W, C_out, R, S, stride, pad, bits, flags=0):
+    return dsq_conv_desc(N, C_in, H, W, C_out, R, S, stride, pad, bits, flags)
 
 
-def alloc_layer(N, C_in, H, W, C_out, R, S, stride, pad, bits, device="cuda", with_acc=False):
+def alloc_layer(N, C_in, H, W, C_out, R, S, stride, pad, bits, device="cuda", with_acc=False, flags=0):
     """Device buffers for one layer, sized by the library's own size queries."""
     Ho = (H + 2 * pad - R) // stride + 1
     Wo = (W + 2 * pad - S) // stride + 1
     u8 = dict(dtype=torch.uint8, device=device)
     return LayerBuffers(
-        desc=make_desc(N, C_in, H, W, C_out, R, S, stride, pad, bits),
+        desc=make_desc(N, C_in, H, W, C_out, R, S, stride, pad, bits, flags),
         act_packed=torch.empty(dsq_act_packed_bytes(N, H, W, C_in, bits), **u8),
         pix_code_sum=torch.empty(N * H * W, dtype=torch.int32, device=device),
         w_packed=torch.empty(dsq_wgt_packed_bytes(C_out, C_in, R, S, bits), **u8),

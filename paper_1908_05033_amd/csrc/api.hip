@@ -9,9 +9,6 @@
 
 namespace {
 
-int g_conv_kernel = 0;   // 0 auto, 1 simple, 2 patch (auto tile), 3..6 patch with a fixed tile, 7 split-K 1x1
-int g_conv_policy = 0;   // 0: shortest single call, 1: several calls in flight
-
 bool bits_ok(int bits) { return bits >= 1 && bits <= 4; }
 bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
 // A clip range must be finite, ordered, and of a width whose step Delta = (u - l) / (2^b - 1)
@@ -130,6 +127,7 @@ dsq_status conv_args(const dsq_conv_desc *d, const void *act_packed, const int32
     if (9LL * d->R * d->S * Cp > (1LL << 22)) return DSQ_ERR_UNSUPPORTED;
     if ((long long)d->N * Ho * Wo * dsq_round_up(d->C_out, 64) > kMaxElems) return DSQ_ERR_UNSUPPORTED;
     if ((long long)d->N * Ho * Wo + 1024 > kMaxElems) return DSQ_ERR_UNSUPPORTED;
+    if ((d->flags & ~(15 | DSQ_CONV_MANY_IN_FLIGHT)) != 0 || (d->flags & 15) > 7) return DSQ_ERR_UNSUPPORTED;
     if (!aligned16(act_packed) || !aligned16(pix_code_sum) || !aligned16(w_packed) || !aligned16(w_aux))
         return DSQ_ERR_ALIGN;
 
@@ -137,7 +135,8 @@ dsq_status conv_args(const dsq_conv_desc *d, const void *act_packed, const int32
     a.stride = d->stride; a.pad = d->pad; a.bits = d->bits;
     a.Ho = Ho; a.Wo = Wo; a.Cp = Cp; a.Cop = Cop;
     a.act = act_packed; a.pix_sum = pix_code_sum; a.l_a = l_a; a.u_a = u_a;
-    a.many_in_flight = g_conv_policy;
+    a.kernel = d->flags & 15;
+    a.many_in_flight = (d->flags & DSQ_CONV_MANY_IN_FLIGHT) != 0;
     // (one IEEE binary32 subtraction and division: the value dsq_delta gives on the device)
     a.delta_a = (u_a - l_a) / (float)((1 << d->bits) - 1);
     a.wq = w_packed;
@@ -196,36 +195,27 @@ void quantizer_thresholds(float l, float u, int bits, float thr[16])
     }
 }
 
-// Chained mode: the kernels add every workgroup's share of a pixel's code sum
-// to the next layer's sums, which therefore start at zero (a fill kernel, not a
-// memset: callers may be capturing a graph).
-bool clear_next_sums(const DsqConvArgs &a, hipStream_t stream)
-{
-    if (!a.rq) return true;
-    return dsq_launch_fill_zero(a.rq_pix, (size_t)a.N * a.Ho * a.Wo, stream) == hipSuccess;
-}
-
+// Every launcher checks its plan and kernel attributes first and only then
+// enqueues (in chained mode: the clearing of the next layer's pixel sums where
+// workgroups add to them, then the kernel), so that an error leaves the stream
+// untouched.
 dsq_status launch_conv(const DsqConvArgs &a, hipStream_t stream)
 {
+    // 0 auto, 1 simple, 2 patch (auto tile), 3..6 patch with a fixed tile, 7 split-K 1x1
+    const int kernel = a.kernel;
     hipError_t e;
-    if (g_conv_kernel == 7 || g_conv_kernel == 0) {
-        const bool fc_ok = g_conv_kernel == 7 ? dsq_conv_fc_supported(a) : dsq_conv_fc_preferred(a);
-        if (g_conv_kernel == 7 && !fc_ok) return DSQ_ERR_UNSUPPORTED;
+    if (kernel == 7 || kernel == 0) {
+        const bool fc_ok = kernel == 7 ? dsq_conv_fc_supported(a) : dsq_conv_fc_preferred(a);
+        if (kernel == 7 && !fc_ok) return DSQ_ERR_UNSUPPORTED;
         if (fc_ok) {
-            if (!clear_next_sums(a, stream)) return DSQ_ERR_HIP;
             e = dsq_launch_conv_fc(a, stream);
             return e == hipSuccess ? DSQ_OK : DSQ_ERR_HIP;
         }
     }
-    const int force_tile = g_conv_kernel >= 3 ? g_conv_kernel - 3 : -1;
-    const bool patch_ok = g_conv_kernel != 1 && dsq_conv_patch_supported(a, force_tile);
-    if (g_conv_kernel >= 2 && !patch_ok) return DSQ_ERR_UNSUPPORTED;
-    if (!patch_ok) {
-        if (!clear_next_sums(a, stream)) return DSQ_ERR_HIP;
-        e = dsq_launch_conv_simple(a, stream);
-    } else {
-        e = dsq_launch_conv_patch(a, force_tile, stream);     // (clears them itself where it adds to them)
-    }
+    const int force_tile = kernel >= 3 ? kernel - 3 : -1;
+    const bool patch_ok = kernel != 1 && dsq_conv_patch_supported(a, force_tile);
+    if (kernel >= 2 && !patch_ok) return DSQ_ERR_UNSUPPORTED;
+    e = patch_ok ? dsq_launch_conv_patch(a, force_tile, stream) : dsq_launch_conv_simple(a, stream);
     return e == hipSuccess ? DSQ_OK : DSQ_ERR_HIP;
 }
 
@@ -342,20 +332,6 @@ dsq_status dsq_soft_quantize_bwd(const float *x, const float *grad_y, size_t n, 
     if (st != DSQ_OK) return st;
     return dsq_launch_soft_bwd(x, grad_y, grad_x, n, p, grad_alpha_l_u, (hipStream_t)hip_stream) == hipSuccess
                ? DSQ_OK : DSQ_ERR_HIP;
-}
-
-int dsq_set_conv_kernel(int which)
-{
-    int prev = g_conv_kernel;
-    if (which >= 0 && which <= 7) g_conv_kernel = which;
-    return prev;
-}
-
-int dsq_set_conv_policy(int policy)
-{
-    int prev = g_conv_policy;
-    if (policy == 0 || policy == 1) g_conv_policy = policy;
-    return prev;
 }
 
 const char *dsq_status_string(dsq_status s)

@@ -15,7 +15,8 @@ struct DsqConvArgs {
     const int32_t *pix_sum;   // [N*H*W]
     float l_a, u_a;
     float delta_a;            // (u_a - l_a) / (2^bits - 1) in binary32, computed by the host
-    int many_in_flight;       // host only: the caller keeps several calls in flight (see dsq_set_conv_policy)
+    int kernel;               // host only: DSQ_CONV_KERNEL value of the call (0 = automatic)
+    int many_in_flight;       // host only: the caller keeps several calls in flight (DSQ_CONV_MANY_IN_FLIGHT)
     const void *wq;           // packed weights
     const float *delta_w;     // [Cop]
     const float *l_w;         // [Cop]

@@ -1,4 +1,4 @@
-"""Per-layer timing of dsq_quantize_act and dsq_conv2d on one GPU.
+"""Per-layer timing of dsq_quantize_act, dsq_conv2d and dsq_conv2d_requant on one GPU.
 
     python -m paper_1908_05033_amd.layer_bench --cfg 3 [--bits 4] [--kernel 0] [--chained]
     python -m paper_1908_05033_amd.layer_bench --fc [--kernel 2]      (fully connected layers)
@@ -6,18 +6,26 @@
 For every layer of a config (shapes from :mod:`paper_1908_05033_amd.inputs`)
 it prints one JSON line: kernel time, effective int-TOPS (2*MACs/s, padding taps
 included), fraction of the matrix peak of the instruction the layer runs on
-(int8: 5000 TOP/s; 2-bit layers use the FP4 form: 10100), algorithmic bytes (packed codes in,
-packed weights, pixel sums, fp32 out) and the GB/s they amount to.  Inputs are
-random tensors drawn on the GPU (timing does not depend on the values); launches
-are captured in a hipGraph that rotates over enough buffer sets to exceed the
-256 MB last-level cache, and timed with events on the launch stream.
+(int8: 5000 TOP/s; 1- and 2-bit layers use the FP4 form: 10100), algorithmic
+bytes (packed codes in, packed weights, pixel sums, fp32 out) and the GB/s they
+amount to.  Inputs are random tensors of the config's distribution drawn on the
+GPU (timing does not depend on the values).  Each call is timed twice:
 
-With --chained it also times dsq_conv2d_requant (the layer's output written as
-the next layer's packed codes) and, for comparison, the two calls it replaces:
-dsq_conv2d to fp32 followed by dsq_quantize_act of that tensor.
+  cold   launches captured in a hipGraph that rotates over as many buffer sets
+         as it takes to exceed 600 MB, so that the 256 MB last-level cache
+         cannot serve them (what a layer inside a large network sees);
+  warm   the same graph over two buffer sets only, whose tensors stay in the
+         last-level cache when they fit (what a small layer called in a tight
+         loop sees).
+
+Both are timed with events on the launch stream.  With --chained it also times
+dsq_conv2d_requant (the layer's output written as the next layer's packed
+codes) and, for comparison, the two calls it replaces: dsq_conv2d to fp32
+followed by dsq_quantize_act of that tensor.
 """
 import argparse
 import json
+import math
 
 import torch
 
@@ -25,118 +33,175 @@ from . import binding as B
 from . import inputs
 
 INT8_PEAK_TOPS = 5000.0      # dense int8 matrix peak (3- and 4-bit layers)
-FP4_PEAK_TOPS = 10100.0      # dense FP4 matrix peak (2-bit layers run on the FP4 instruction)
+FP4_PEAK_TOPS = 10100.0      # dense FP4 matrix peak (1- and 2-bit layers run on the FP4 instruction)
 HBM_PEAK_GBS = 8000.0
+RIDGE_INT8 = INT8_PEAK_TOPS * 1e12 / (HBM_PEAK_GBS * 1e9)     # ops per byte where the two bounds meet
+MAX_SETS = 1024              # most buffer sets (graph nodes) of one measurement
+
+# clip bound of |N(0,1)| activations at the percentile the config's recipe names
+HALF_NORMAL_Q = {99.9: 3.2905, 99.5: 2.8070}
 
 
-def _time_graph(fn, bufs, stream, reps):
+def matrix_peak_tops(bits):
+    return FP4_PEAK_TOPS if bits <= 2 else INT8_PEAK_TOPS
+
+
+def time_graph(fns, stream, reps, warm_reps=1):
+    """Average seconds per call of the calls ``fns`` (closures without
+    arguments), captured once as a hipGraph and replayed ``reps`` times
+    between two events on the launch stream."""
     g = torch.cuda.CUDAGraph()
     with torch.cuda.graph(g, stream=stream):
-        for b in bufs:
-            fn(b)
+        for fn in fns:
+            fn()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     with torch.cuda.stream(stream):
-        g.replay()
+        for _ in range(warm_reps):
+            g.replay()
         torch.cuda.synchronize()
         e0.record(stream)
         for _ in range(reps):
             g.replay()
         e1.record(stream)
         torch.cuda.synchronize()
-    return e0.elapsed_time(e1) * 1e-3 / (reps * len(bufs))
+    return e0.elapsed_time(e1) * 1e-3 / (reps * len(fns))
 
 
-def bench_layer(L, kernel=0, min_bytes=600e6, max_sets=16, reps=5, chained=False):
-    dev = "cuda"
-    gen = torch.Generator(device=dev).manual_seed(inputs.BASE_SEED)
-    in_bytes = L.N * L.H * L.W * L.C_in * 4
-    out_bytes = L.N * L.Ho * L.Wo * L.C_out * 4
-    code_bytes = B.dsq_act_packed_bytes(L.N, L.H, L.W, L.C_in, L.bits)
-    pix_bytes = L.N * L.H * L.W * 4
-    w_bytes = B.dsq_wgt_packed_bytes(L.C_out, L.C_in, L.R, L.S, L.bits)
-    per_set = in_bytes + out_bytes + code_bytes + pix_bytes
-    sets = int(min(max_sets, max(2, -(-min_bytes // per_set))))
+class LayerState:
+    """Device buffers and call closures of one layer over ``sets`` buffer sets.
+    Weights are packed once (model-load time)."""
 
-    w = torch.randn((L.C_out, L.C_in, L.R, L.S), device=dev, generator=gen) * 0.05
-    uw = w.reshape(L.C_out, -1).abs().amax(dim=1).contiguous()
-    lw = (-uw).contiguous()
-    bufs = []
-    for _ in range(sets):
-        b = B.alloc_layer(L.N, L.C_in, L.H, L.W, L.C_out, L.R, L.S, L.stride, L.pad, L.bits)
-        b.x = torch.randn((L.N, L.H, L.W, L.C_in), device=dev, generator=gen).abs_()
-        bufs.append(b)
-    wp, aux = bufs[0].w_packed, bufs[0].w_aux
-    B.dsq_pack_weights(w, lw, uw, None, L.C_out, L.C_in, L.R, L.S, L.bits, wp, aux)
-    l_a, u_a = 0.0, 2.5
+    def __init__(self, L, sets, flags=0, chained=False, u_a=2.5, gen=None, bits_next=None):
+        dev = "cuda"
+        self.L = L
+        gen = gen or torch.Generator(device=dev).manual_seed(inputs.BASE_SEED)
+        self.in_bytes = L.N * L.H * L.W * L.C_in * 4
+        self.out_bytes = L.N * L.Ho * L.Wo * L.C_out * 4
+        self.code_bytes = B.dsq_act_packed_bytes(L.N, L.H, L.W, L.C_in, L.bits)
+        self.pix_bytes = L.N * L.H * L.W * 4
+        self.w_bytes = B.dsq_wgt_packed_bytes(L.C_out, L.C_in, L.R, L.S, L.bits)
+        w = torch.randn((L.C_out, L.C_in, L.R, L.S), device=dev, generator=gen) * math.sqrt(2.0 / (L.C_in * L.R * L.S))
+        wf = w.reshape(L.C_out, -1)
+        self.w, self.lw, self.uw = w, wf.amin(dim=1).contiguous(), wf.amax(dim=1).contiguous()
+        self.bufs = []
+        for _ in range(sets):
+            b = B.alloc_layer(L.N, L.C_in, L.H, L.W, L.C_out, L.R, L.S, L.stride, L.pad, L.bits, flags=flags)
+            b.x = torch.randn((L.N, L.H, L.W, L.C_in), device=dev, generator=gen).abs_()
+            self.bufs.append(b)
+        self.wp, self.aux = self.bufs[0].w_packed, self.bufs[0].w_aux
+        self.l_a, self.u_a = 0.0, float(u_a)
+        self.pack()
+        self.chained = chained
+        if chained:
+            self.bits_next = bits_next or L.bits
+            self.scale = torch.rand(L.C_out, device=dev, generator=gen) + 0.5
+            self.shift = torch.randn(L.C_out, device=dev, generator=gen) * 0.1
+            self.l_n, self.u_n = 0.0, 1.0
+            self.next_bytes = B.dsq_act_packed_bytes(L.N, L.Ho, L.Wo, L.C_out, self.bits_next)
+            for b in self.bufs:
+                b.codes_next = torch.empty(self.next_bytes, dtype=torch.uint8, device=dev)
+                b.pix_next = torch.empty(L.N * L.Ho * L.Wo, dtype=torch.int32, device=dev)
 
-    def quant(b):
-        B.dsq_quantize_act(b.x, B.DSQ_NHWC, L.N, L.C_in, L.H, L.W, l_a, u_a, L.bits,
+    @staticmethod
+    def bytes_per_set(L):
+        return (L.N * L.H * L.W * L.C_in * 4 + L.N * L.Ho * L.Wo * L.C_out * 4 +
+                B.dsq_act_packed_bytes(L.N, L.H, L.W, L.C_in, L.bits) + L.N * L.H * L.W * 4)
+
+    def pack(self):
+        L = self.L
+        B.dsq_pack_weights(self.w, self.lw, self.uw, None, L.C_out, L.C_in, L.R, L.S, L.bits, self.wp, self.aux)
+
+    def quant(self, b):
+        L = self.L
+        B.dsq_quantize_act(b.x, B.DSQ_NHWC, L.N, L.C_in, L.H, L.W, self.l_a, self.u_a, L.bits,
                            b.act_packed, b.pix_code_sum)
 
-    def conv(b):
-        B.dsq_conv2d(b.desc, b.act_packed, b.pix_code_sum, l_a, u_a, wp, aux, b.out, B.DSQ_NHWC, None)
+    def conv(self, b):
+        B.dsq_conv2d(b.desc, b.act_packed, b.pix_code_sum, self.l_a, self.u_a, self.wp, self.aux, b.out,
+                     B.DSQ_NHWC, None)
 
-    if chained:
-        scale = torch.rand(L.C_out, device=dev, generator=gen) + 0.5
-        shift = torch.randn(L.C_out, device=dev, generator=gen) * 0.1
-        l_n, u_n = 0.0, 1.0
-        next_bytes = B.dsq_act_packed_bytes(L.N, L.Ho, L.Wo, L.C_out, L.bits)
-        for b in bufs:
-            b.codes_next = torch.empty(next_bytes, dtype=torch.uint8, device=dev)
-            b.pix_next = torch.empty(L.N * L.Ho * L.Wo, dtype=torch.int32, device=dev)
+    def conv_chained(self, b):
+        B.dsq_conv2d_requant(b.desc, b.act_packed, b.pix_code_sum, self.l_a, self.u_a, self.wp, self.aux,
+                             self.scale, self.shift, True, self.l_n, self.u_n, self.bits_next,
+                             b.codes_next, b.pix_next)
 
-    def conv_chained(b):
-        B.dsq_conv2d_requant(b.desc, b.act_packed, b.pix_code_sum, l_a, u_a, wp, aux, scale, shift, True,
-                             l_n, u_n, L.bits, b.codes_next, b.pix_next)
-
-    def quant_next(b):      # what the chained call saves: quantizing the fp32 output for the next layer
-        B.dsq_quantize_act(b.out, B.DSQ_NHWC, L.N, L.C_out, L.Ho, L.Wo, l_n, u_n, L.bits,
+    def quant_next(self, b):
+        """What the chained call saves: quantizing the fp32 output for the next layer."""
+        L = self.L
+        B.dsq_quantize_act(b.out, B.DSQ_NHWC, L.N, L.C_out, L.Ho, L.Wo, self.l_n, self.u_n, self.bits_next,
                            b.codes_next, b.pix_next)
 
-    prev = B.dsq_set_conv_kernel(kernel)
-    try:
-        stream = torch.cuda.Stream()
-        with torch.cuda.stream(stream):
-            for b in bufs:
-                quant(b)
-                conv(b)
-                if chained:
-                    conv_chained(b)
-            torch.cuda.synchronize()
-        tq = _time_graph(quant, bufs, stream, reps)
-        tc = _time_graph(conv, bufs, stream, reps)
-        if chained:
-            tcc = _time_graph(conv_chained, bufs, stream, reps)
-            tqn = _time_graph(quant_next, bufs, stream, reps)
-    finally:
-        B.dsq_set_conv_kernel(prev)
-    # algorithmic conv bytes: packed weights are counted at the packed code width
-    cont = 2 if L.bits <= 2 else 4
-    w_alg = L.C_out * L.C_in * L.R * L.S * cont // 8
-    conv_bytes = code_bytes + pix_bytes + w_alg + out_bytes
-    quant_bytes = in_bytes + code_bytes + pix_bytes
+    def calls(self, method, bufs=None):
+        return [(lambda b=b: method(b)) for b in (bufs if bufs is not None else self.bufs)]
+
+    # algorithmic bytes per call (packed weights counted at the packed code width)
+    def conv_alg_bytes(self):
+        L = self.L
+        cont = 2 if L.bits <= 2 else 4
+        return self.code_bytes + self.pix_bytes + L.C_out * L.C_in * L.R * L.S * cont // 8 + self.out_bytes
+
+    def chained_alg_bytes(self):
+        L = self.L
+        cont = 2 if L.bits <= 2 else 4
+        return (self.code_bytes + self.pix_bytes + L.C_out * L.C_in * L.R * L.S * cont // 8 +
+                self.next_bytes + L.N * L.Ho * L.Wo * 4)
+
+    def quant_alg_bytes(self):
+        return self.in_bytes + self.code_bytes + self.pix_bytes
+
+
+def cold_sets(L, min_bytes=600e6):
+    return int(min(MAX_SETS, max(2, -(-min_bytes // LayerState.bytes_per_set(L)))))
+
+
+def bench_layer(L, kernel=0, many_in_flight=False, min_bytes=600e6, reps=5, chained=False, u_a=2.5):
+    sets = cold_sets(L, min_bytes)
+    flags = B.DSQ_CONV_KERNEL(kernel) | (B.DSQ_CONV_MANY_IN_FLIGHT if many_in_flight else 0)
+    st = LayerState(L, sets, flags=flags, chained=chained, u_a=u_a)
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        for b in st.bufs:
+            st.quant(b)
+            st.conv(b)
+            if chained:
+                st.conv_chained(b)
+        torch.cuda.synchronize()
+    warm = st.bufs[:2]
+    warm_reps = max(reps, reps * sets // 8)
+    tq = time_graph(st.calls(st.quant), stream, reps)
+    tc = time_graph(st.calls(st.conv), stream, reps)
+    tq_warm = time_graph(st.calls(st.quant, warm), stream, warm_reps)
+    tc_warm = time_graph(st.calls(st.conv, warm), stream, warm_reps)
+    conv_bytes, quant_bytes = st.conv_alg_bytes(), st.quant_alg_bytes()
     tops = 2.0 * L.macs / tc / 1e12
+    peak = matrix_peak_tops(L.bits)
     extra = {}
     if chained:
-        ch_bytes = code_bytes + pix_bytes + w_alg + next_bytes + L.N * L.Ho * L.Wo * 4
+        tcc = time_graph(st.calls(st.conv_chained), stream, reps)
+        tqn = time_graph(st.calls(st.quant_next), stream, reps)
+        tcc_warm = time_graph(st.calls(st.conv_chained, warm), stream, warm_reps)
+        ch_bytes = st.chained_alg_bytes()
         extra = {
-            "chained_us": round(tcc * 1e6, 2), "chained_TOPS": round(2.0 * L.macs / tcc / 1e12, 1),
+            "chained_us": round(tcc * 1e6, 2), "chained_warm_us": round(tcc_warm * 1e6, 2),
+            "chained_TOPS": round(2.0 * L.macs / tcc / 1e12, 1),
             "chained_alg_MB": round(ch_bytes / 1e6, 2), "chained_GBps": round(ch_bytes / tcc / 1e9, 1),
             "unchained_us": round((tc + tqn) * 1e6, 2), "quant_next_us": round(tqn * 1e6, 2),
-            "chained_speedup": round((tc + tqn) / tcc, 2),
+            "chained_speedup": round((tc + tqn) / tcc, 2), "chained_vs_plain_conv": round(tc / tcc, 2),
         }
     return {**extra, **{
         "layer": L.name, "bits": L.bits, "count": L.count,
         "gemm_MxNxK": [L.N * L.Ho * L.Wo, L.C_out, L.C_in * L.R * L.S],
-        "conv_us": round(tc * 1e6, 2), "conv_TOPS": round(tops, 1),
+        "conv_us": round(tc * 1e6, 2), "conv_warm_us": round(tc_warm * 1e6, 2), "conv_TOPS": round(tops, 1),
         "conv_frac_int8_peak": round(tops / INT8_PEAK_TOPS, 4),
-        "matrix_peak_TOPS": FP4_PEAK_TOPS if L.bits <= 2 else INT8_PEAK_TOPS,
-        "conv_frac_matrix_peak": round(tops / (FP4_PEAK_TOPS if L.bits <= 2 else INT8_PEAK_TOPS), 4),
+        "matrix_peak_TOPS": peak,
+        "conv_frac_matrix_peak": round(tops / peak, 4),
         "conv_alg_MB": round(conv_bytes / 1e6, 2), "conv_GBps": round(conv_bytes / tc / 1e9, 1),
         "conv_frac_hbm_peak": round(conv_bytes / tc / 1e9 / HBM_PEAK_GBS, 4),
-        "quant_us": round(tq * 1e6, 2), "quant_GBps": round(quant_bytes / tq / 1e9, 1),
+        "quant_us": round(tq * 1e6, 2), "quant_warm_us": round(tq_warm * 1e6, 2),
+        "quant_GBps": round(quant_bytes / tq / 1e9, 1),
         "quant_frac_hbm_peak": round(quant_bytes / tq / 1e9 / HBM_PEAK_GBS, 4),
-        "buffer_sets": sets, "w_buffer_bytes": w_bytes,
+        "buffer_sets": sets, "cold_working_set_MB": round(sets * LayerState.bytes_per_set(L) / 1e6, 1),
+        "w_buffer_bytes": st.w_bytes,
     }}
 
 
@@ -149,10 +214,10 @@ def main():
     ap.add_argument("--kernel", type=int, default=0)
     ap.add_argument("--layer", type=int, default=None)
     ap.add_argument("--chained", action="store_true")
-    ap.add_argument("--policy", type=int, default=0,
-                    help="dsq_set_conv_policy value (0 = shortest single call: kernels are timed one at a time here)")
+    ap.add_argument("--many-in-flight", action="store_true",
+                    help="pass DSQ_CONV_MANY_IN_FLIGHT (the default optimises a single call; kernels are "
+                         "timed one at a time here)")
     a = ap.parse_args()
-    B.dsq_set_conv_policy(a.policy)
     if a.fc:
         layers = [inputs.ConvLayer("fc.%d-%d@batch%d" % (ci, co, n), n, ci, 1, 1, co, 1, 1, 1, 0, b)
                   for n, ci, co, b in ((64, 4096, 4096, 4), (64, 4096, 4096, 2), (256, 4096, 4096, 4),
@@ -165,7 +230,7 @@ def main():
         layers = [layers[a.layer]]
     tot_t, tot_macs = 0.0, 0
     for L in layers:
-        r = bench_layer(L, kernel=a.kernel, chained=a.chained)
+        r = bench_layer(L, kernel=a.kernel, many_in_flight=a.many_in_flight, chained=a.chained)
         print(json.dumps(r), flush=True)
         tot_t += (r["conv_us"] + r["quant_us"]) * 1e-6 * L.count
         tot_macs += L.macs * L.count

@@ -23,12 +23,15 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--cfg", type=int, default=2)
     ap.add_argument("--layer", type=int, default=0)
-    ap.add_argument("--sets", type=int, default=48)
-    ap.add_argument("--policy", type=int, default=1,
-                    help="dsq_set_conv_policy value (1 = several calls in flight, what bench.py runs with)")
+    ap.add_argument("--bits", type=int, default=None)
+    ap.add_argument("--sets", type=int, default=0, help="buffer sets (0 = enough to exceed 600 MB, at most 48)")
+    ap.add_argument("--many-in-flight", action="store_true", help="pass DSQ_CONV_MANY_IN_FLIGHT")
     a = ap.parse_args()
-    B.dsq_set_conv_policy(a.policy)
-    L = inputs.config_layers(a.cfg)[a.layer]
+    flags = B.DSQ_CONV_MANY_IN_FLIGHT if a.many_in_flight else 0
+    L = inputs.config_layers(a.cfg, a.bits)[a.layer]
+    per_set = (L.N * L.H * L.W * L.C_in * 4 + L.N * L.Ho * L.Wo * L.C_out * 4 +
+               B.dsq_act_packed_bytes(L.N, L.H, L.W, L.C_in, L.bits) + L.N * L.H * L.W * 4)
+    a.sets = a.sets or int(min(48, max(2, -(-600e6 // per_set))))
     dev = "cuda"
     gen = torch.Generator(device=dev).manual_seed(inputs.BASE_SEED)
 
@@ -43,7 +46,7 @@ def main():
     lw = (-uw).contiguous()
     bufs = []
     for _ in range(a.sets):
-        b = B.alloc_layer(L.N, L.C_in, L.H, L.W, L.C_out, L.R, L.S, L.stride, L.pad, L.bits)
+        b = B.alloc_layer(L.N, L.C_in, L.H, L.W, L.C_out, L.R, L.S, L.stride, L.pad, L.bits, flags=flags)
         b.x = torch.randn((L.N, L.H, L.W, L.C_in), device=dev, generator=gen).abs_()
         bufs.append(b)
     wp, aux = bufs[0].w_packed, bufs[0].w_aux

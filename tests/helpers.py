@@ -72,7 +72,7 @@ def split_aux(aux_u8, C_out, R):
 
 
 def run_layer_gpu(layer, inp, x_layout=B.DSQ_NHWC, out_layout=B.DSQ_NHWC, w_codes=None,
-                  kernel=0, with_acc=True):
+                  kernel=0, with_acc=True, many_in_flight=False):
     """quantize + pack + conv through the C ABI.  Returns a dict of host arrays
     (out / acc always as [N, C_out, Ho, Wo])."""
     L = layer
@@ -95,12 +95,9 @@ def run_layer_gpu(layer, inp, x_layout=B.DSQ_NHWC, out_layout=B.DSQ_NHWC, w_code
         if with_acc:
             buf.acc = torch.empty((L.N, L.C_out, L.Ho, L.Wo), dtype=torch.int32, device="cuda")
     buf.out.fill_(float("nan"))
-    prev = B.dsq_set_conv_kernel(kernel)
-    try:
-        B.dsq_conv2d(buf.desc, buf.act_packed, buf.pix_code_sum, inp["l_a"], inp["u_a"],
-                     buf.w_packed, buf.w_aux, buf.out, out_layout, buf.acc)
-    finally:
-        B.dsq_set_conv_kernel(prev)
+    buf.desc.flags = B.DSQ_CONV_KERNEL(kernel) | (B.DSQ_CONV_MANY_IN_FLIGHT if many_in_flight else 0)
+    B.dsq_conv2d(buf.desc, buf.act_packed, buf.pix_code_sum, inp["l_a"], inp["u_a"],
+                 buf.w_packed, buf.w_aux, buf.out, out_layout, buf.acc)
     torch.cuda.synchronize()
     out = buf.out.cpu().numpy()
     acc = buf.acc.cpu().numpy() if with_acc else None
@@ -131,7 +128,7 @@ def assert_out_close(gpu, ref, delta_a, delta_w, rel=1e-5):
     bad = err > rel * np.abs(r) + floor
     assert not bad.any(), "%d elements off, worst %.3e (ref %.3e)" % (
         bad.sum(), err.max(), np.abs(r).max())
-    assert err.max() <= rel * np.abs(r).max() + floor.max()
+    assert err.max() <= rel * np.abs(r).max()
 
 
 def pack_codes_reference(oc, bits):

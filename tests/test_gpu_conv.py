@@ -209,6 +209,32 @@ def test_largest_codes_at_the_deepest_dot_product_the_library_accepts(bits, kern
     assert np.array_equal(got["acc"], acc)
 
 
+@pytest.mark.parametrize("kernel", [0, 1, 3, 6])
+@pytest.mark.parametrize("bits", [2, 4])
+@pytest.mark.parametrize("C_in", [51712, 4608])
+def test_near_limit_accumulators_fed_by_small_odd_products(bits, kernel, C_in):
+    """The 1/2-bit path sums quarter-unit products in the fp32 accumulators of the
+    FP4 matrix instruction.  Here the accumulators climb to within a few percent
+    of the deepest sum the library accepts (codes mostly at the top) while a
+    scattered subset of activation and weight codes is 1 or 2, so that single
+    quarter units (1 x 1), three (1 x 3) and six (2 x 3) keep arriving at an accumulator that is already
+    large: any loss of low bits in the instruction's alignment or in the order of
+    its partial sums would change the integer.  Codes differ from tap to tap, pixel
+    to pixel and channel to channel."""
+    top = (1 << bits) - 1
+    rng = np.random.default_rng(1000 * bits + C_in)
+    layer, inp = inputs.small_random_case(5, 1, C_in, 4, 5, 48, 3, 1, 1, bits, l_a=0.0, u_a=float(top), asym_w=False)
+    a_codes = np.where(rng.random((1, C_in, 4, 5)) < 0.07, rng.integers(1, 3, (1, C_in, 4, 5)), top).astype(np.uint8)
+    w_codes = np.where(rng.random((48, C_in, 3, 3)) < 0.05, rng.integers(1, 3, (48, C_in, 3, 3)), top).astype(np.uint8)
+    inp["x"] = torch.from_numpy(a_codes.astype(np.float32))        # Delta_a = 1, l_a = 0: x is its own code
+    got = _run(layer, inp, kernel, w_codes=w_codes)
+    a_code, _ = oracle_layer(layer, inp, w_codes)
+    assert np.array_equal(a_code, a_codes)
+    acc = oracle.conv_codes(a_code, w_codes, 1, 1)
+    assert acc.max() > 0.85 * top * top * 9 * C_in and len(np.unique(acc % 4)) == 4
+    assert np.array_equal(got["acc"], acc)
+
+
 @pytest.mark.parametrize("kernel", [0, 1, 3, 4, 6])
 def test_binary_layer_is_the_convolution_of_signs(kernel):
     """bits = 1 with (l, u) = (-1, +1) is the binary quantizer of Sec. 3.1
@@ -237,12 +263,9 @@ def _check_mixed_widths(bits_a, bits_w, kernel, geom):
     B.dsq_pack_weights_for(inp["w"].contiguous().cuda(), torch.from_numpy(inp["l_w"]).cuda(),
                            torch.from_numpy(inp["u_w"]).cuda(), None, L.C_out, L.C_in, R, R, bits_w, bits_a,
                            buf.w_packed, buf.w_aux)
-    prev = B.dsq_set_conv_kernel(kernel)
-    try:
-        B.dsq_conv2d(buf.desc, buf.act_packed, buf.pix_code_sum, inp["l_a"], inp["u_a"], buf.w_packed, buf.w_aux,
-                     buf.out, B.DSQ_NHWC, buf.acc)
-    finally:
-        B.dsq_set_conv_kernel(prev)
+    buf.desc.flags = B.DSQ_CONV_KERNEL(kernel)
+    B.dsq_conv2d(buf.desc, buf.act_packed, buf.pix_code_sum, inp["l_a"], inp["u_a"], buf.w_packed, buf.w_aux,
+                 buf.out, B.DSQ_NHWC, buf.acc)
     torch.cuda.synchronize()
     a_code = oracle.quantize(inp["x"].numpy(), inp["l_a"], inp["u_a"], bits_a)
     w_code = oracle.quantize_weights(inp["w"].numpy(), inp["l_w"], inp["u_w"], bits_w)
@@ -293,12 +316,9 @@ def test_largest_tensors_the_library_accepts(kernel):
     B.dsq_quantize_act(x, B.DSQ_NHWC, N, C, H, W, l_a, u_a, bits, buf.act_packed, buf.pix_code_sum)
     B.dsq_pack_weights(w.cuda(), torch.from_numpy(lw).cuda(), torch.from_numpy(uw).cuda(), None, C, C, 1, 1, bits,
                        buf.w_packed, buf.w_aux)
-    prev = B.dsq_set_conv_kernel(kernel)
-    try:
-        B.dsq_conv2d(buf.desc, buf.act_packed, buf.pix_code_sum, l_a, u_a, buf.w_packed, buf.w_aux, buf.out,
-                     B.DSQ_NHWC, buf.acc)
-    finally:
-        B.dsq_set_conv_kernel(prev)
+    buf.desc.flags = B.DSQ_CONV_KERNEL(kernel)
+    B.dsq_conv2d(buf.desc, buf.act_packed, buf.pix_code_sum, l_a, u_a, buf.w_packed, buf.w_aux, buf.out,
+                 B.DSQ_NHWC, buf.acc)
     torch.cuda.synchronize()
     rs = np.random.RandomState(5)
     sample = np.unique(np.concatenate([np.arange(2048), np.arange(P - 2048, P), rs.randint(0, P, 4096)]))
@@ -318,13 +338,10 @@ def test_largest_tensors_the_library_accepts(kernel):
     l_n, u_n, bits_n = 0.0, float(np.float32(1.9)), 4
     codes_n = torch.empty((B.dsq_act_packed_bytes(N, H, W, C, bits_n),), dtype=torch.uint8, device="cuda")
     pix_n = torch.empty((P,), dtype=torch.int32, device="cuda")
-    prev = B.dsq_set_conv_kernel(kernel)
-    try:
-        B.dsq_conv2d_requant(buf.desc, buf.act_packed, buf.pix_code_sum, l_a, u_a, buf.w_packed, buf.w_aux,
-                             torch.from_numpy(scale).cuda(), torch.from_numpy(shift).cuda(), True, l_n, u_n, bits_n,
-                             codes_n, pix_n)
-    finally:
-        B.dsq_set_conv_kernel(prev)
+    buf.desc.flags = B.DSQ_CONV_KERNEL(kernel)
+    B.dsq_conv2d_requant(buf.desc, buf.act_packed, buf.pix_code_sum, l_a, u_a, buf.w_packed, buf.w_aux,
+                         torch.from_numpy(scale).cuda(), torch.from_numpy(shift).cuda(), True, l_n, u_n, bits_n,
+                         codes_n, pix_n)
     torch.cuda.synchronize()
     want_n = oracle.requantize(ref.astype(np.float32), scale, shift, True, l_n, u_n, bits_n).reshape(len(sample), C)
     got_rows = codes_n.reshape(P, -1)[idx].cpu().numpy()
@@ -348,17 +365,12 @@ def test_largest_tensors_the_library_accepts(kernel):
                                   (1, 576, 6, 6, 96, 1, 1, 0)])
 @pytest.mark.parametrize("bits", [2, 4])
 def test_throughput_policy_gives_the_same_results(geom, bits):
-    """dsq_set_conv_policy(1) only changes how a layer is spread over the chip
+    """DSQ_CONV_MANY_IN_FLIGHT only changes how a layer is spread over the chip
     (one wave group per workgroup where the default uses two): accumulators and
     outputs of layers that the default runs with two groups must not change."""
     N, Ci, H, W, Co, R, stride, pad = geom
     layer, inp = inputs.small_random_case(41 + bits, N, Ci, H, W, Co, R, stride, pad, bits, l_a=0.0, u_a=2.1)
-    prev = B.dsq_set_conv_policy(1)
-    try:
-        got, ref = _check_full(layer, inp, 0)
-        got_rq = None
-    finally:
-        B.dsq_set_conv_policy(prev)
+    got, ref = _check_full(layer, inp, 0, many_in_flight=True)
     base = _run(layer, inp, 0)
     assert np.array_equal(got["acc"], base["acc"]) and np.array_equal(got["out"], base["out"])
 

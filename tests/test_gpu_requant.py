@@ -23,7 +23,8 @@ pytestmark = pytest.mark.gpu
 KERNELS = [1, 3, 4, 5, 6]
 
 
-def run_requant_gpu(layer, inp, scale, shift, relu, l_n, u_n, bits_n, kernel=0, skip_unsupported=True):
+def run_requant_gpu(layer, inp, scale, shift, relu, l_n, u_n, bits_n, kernel=0, skip_unsupported=True,
+                    many_in_flight=False):
     L = layer
     buf = B.alloc_layer(L.N, L.C_in, L.H, L.W, L.C_out, L.R, L.S, L.stride, L.pad, L.bits)
     xd = inp["x"].permute(0, 2, 3, 1).contiguous().cuda()
@@ -38,7 +39,7 @@ def run_requant_gpu(layer, inp, scale, shift, relu, l_n, u_n, bits_n, kernel=0, 
     pix = torch.full((L.N * L.Ho * L.Wo,), 12345, dtype=torch.int32, device="cuda")
     sc = torch.from_numpy(scale).cuda() if scale is not None else None
     sh = torch.from_numpy(shift).cuda() if shift is not None else None
-    prev = B.dsq_set_conv_kernel(kernel)
+    buf.desc.flags = B.DSQ_CONV_KERNEL(kernel) | (B.DSQ_CONV_MANY_IN_FLIGHT if many_in_flight else 0)
     try:
         B.dsq_conv2d_requant(buf.desc, buf.act_packed, buf.pix_code_sum, inp["l_a"], inp["u_a"],
                              buf.w_packed, buf.w_aux, sc, sh, relu, l_n, u_n, bits_n, codes, pix)
@@ -46,8 +47,6 @@ def run_requant_gpu(layer, inp, scale, shift, relu, l_n, u_n, bits_n, kernel=0, 
         if skip_unsupported and kernel >= 2 and e.status == 5:
             pytest.skip("geometry not supported by the patch kernel")
         raise
-    finally:
-        B.dsq_set_conv_kernel(prev)
     torch.cuda.synchronize()
     c = unpack_act(codes.cpu().numpy(), L.N, L.Ho, L.Wo, L.C_out, bits_n)     # [N, Ho, Wo, Cp]
     return c, pix.cpu().numpy().reshape(L.N, L.Ho, L.Wo), codes, pix, buf
@@ -315,29 +314,26 @@ def test_every_float_bit_pattern_through_the_chained_quantizer(l_n, u_n, bits_n,
         y = np.zeros((1, sub, 1, 1), np.float32)
         return oracle.requantize(y, np.full(sub, 1.5, np.float32), b32.view(np.float32), relu, l_n, u_n, bits_n)
 
-    prev = B.dsq_set_conv_kernel(kernel)
-    try:
-        with ThreadPoolExecutor(workers) as pool:
-            for start in range(0, 1 << 32, n):
-                idx = torch.arange(start, start + n, dtype=torch.int64, device="cuda")
-                shift = torch.where(idx >= (1 << 31), idx - (1 << 32), idx).to(torch.int32).view(torch.float32)
-                del idx
-                for k in range(GROUP):
-                    B.dsq_conv2d_requant(buf.desc, buf.act_packed, buf.pix_code_sum, 0.0, 2.0, buf.w_packed,
-                                         buf.w_aux, scale, shift[k * CO:(k + 1) * CO], relu, l_n, u_n, bits_n,
-                                         codes[k], pix[k])
-                want = np.concatenate(list(pool.map(oracle_part, [(start, k) for k in range(workers)])))
-                oc = torch.from_numpy(want.reshape(-1)).cuda().reshape(GROUP, CO)
-                torch.cuda.synchronize()
-                ref = pack_codes_reference(oc.reshape(-1, 64), bits_n).reshape(GROUP, per_launch)
-                same = torch.equal(codes, ref)
-                sums_same = torch.equal(pix[:, 0], oc.sum(dim=1, dtype=torch.int32))
-                if not (same and sums_same):
-                    bad = (codes != ref).nonzero()
-                    raise AssertionError("range (%r, %r) bits %d relu %s kernel %d: mismatch in the patterns from 0x%08x "
-                                         "(first differing launch/byte %s; codes equal %s, sums equal %s)"
-                                         % (l_n, u_n, bits_n, relu, kernel, start,
-                                            bad[0].tolist() if len(bad) else None, same, sums_same))
-                del shift, oc, ref
-    finally:
-        B.dsq_set_conv_kernel(prev)
+    buf.desc.flags = B.DSQ_CONV_KERNEL(kernel)
+    with ThreadPoolExecutor(workers) as pool:
+        for start in range(0, 1 << 32, n):
+            idx = torch.arange(start, start + n, dtype=torch.int64, device="cuda")
+            shift = torch.where(idx >= (1 << 31), idx - (1 << 32), idx).to(torch.int32).view(torch.float32)
+            del idx
+            for k in range(GROUP):
+                B.dsq_conv2d_requant(buf.desc, buf.act_packed, buf.pix_code_sum, 0.0, 2.0, buf.w_packed,
+                                     buf.w_aux, scale, shift[k * CO:(k + 1) * CO], relu, l_n, u_n, bits_n,
+                                     codes[k], pix[k])
+            want = np.concatenate(list(pool.map(oracle_part, [(start, k) for k in range(workers)])))
+            oc = torch.from_numpy(want.reshape(-1)).cuda().reshape(GROUP, CO)
+            torch.cuda.synchronize()
+            ref = pack_codes_reference(oc.reshape(-1, 64), bits_n).reshape(GROUP, per_launch)
+            same = torch.equal(codes, ref)
+            sums_same = torch.equal(pix[:, 0], oc.sum(dim=1, dtype=torch.int32))
+            if not (same and sums_same):
+                bad = (codes != ref).nonzero()
+                raise AssertionError("range (%r, %r) bits %d relu %s kernel %d: mismatch in the patterns from 0x%08x "
+                                     "(first differing launch/byte %s; codes equal %s, sums equal %s)"
+                                     % (l_n, u_n, bits_n, relu, kernel, start,
+                                        bad[0].tolist() if len(bad) else None, same, sums_same))
+            del shift, oc, ref

@@ -71,15 +71,25 @@ def test_backward(l, u, alpha, bits, n):
 
 def test_largest_tensor():
     """n = 2^31 - 1 elements (the limit, and an odd count): forward values and the
-    elementwise gradient at the head, the tail and a million places in between."""
+    elementwise gradient at the head, the tail and a million places in between,
+    and the three gradient sums over all elements.  The tensor repeats one seeded
+    block of 4 194 301 elements (an odd length, so that the repeats fall differently
+    into the kernel's vectors and workgroups each time); the sums the oracle gives
+    for the block and for the ragged last repeat then add up to the expected sums
+    of the whole tensor, which an element dropped or counted twice anywhere in the
+    2^31 would change."""
     l, u, alpha, bits = -1.0, 2.0, 0.2, 4
     n = (1 << 31) - 1
+    P = 4194301
     g = torch.Generator(device="cuda").manual_seed(inputs.BASE_SEED + 91)
+    xb = torch.empty((P,), dtype=torch.float32, device="cuda").normal_(0.5, 1.2, generator=g)
+    gb = torch.empty((P,), dtype=torch.float32, device="cuda").normal_(0.0, 1.0, generator=g)
     x = torch.empty((n,), dtype=torch.float32, device="cuda")
     gy = torch.empty((n,), dtype=torch.float32, device="cuda")
-    for s in range(0, n, 1 << 27):
-        x[s:s + (1 << 27)].normal_(0.5, 1.2, generator=g)
-        gy[s:s + (1 << 27)].normal_(0.0, 1.0, generator=g)
+    for s in range(0, n, P):
+        m = min(P, n - s)
+        x[s:s + m] = xb[:m]
+        gy[s:s + m] = gb[:m]
     y = torch.empty_like(x)
     B.dsq_soft_quantize_fwd(x, l, u, alpha, bits, y)
     gx = torch.empty_like(x)
@@ -96,7 +106,15 @@ def test_largest_tensor():
     assert np.abs(y[idx].cpu().numpy() - ref).max() <= 2e-6 * max(abs(l), abs(u), u - l)
     dx, da, dl, du = S.partials(xs, lf, uf, af, bits)
     assert np.abs(gx[idx].cpu().numpy() - gs * dx).max() <= 1e-5 * max(1.0, np.abs(dx).max()) * np.abs(gs).max()
-    assert np.isfinite(sums.cpu().numpy()[:3]).all()
+    # the three sums over all 2^31 - 1 elements: whole repeats of the block plus the ragged last one
+    q, r = divmod(n, P)
+    xbh, gbh = xb.cpu().numpy().astype(np.float64), gb.cpu().numpy().astype(np.float64)
+    _, da, dl, du = S.partials(xbh, lf, uf, af, bits)
+    got_sums = sums.cpu().numpy()[:3]
+    for got, d in zip(got_sums, (da, dl, du)):
+        terms = gbh * d
+        want = q * terms.sum() + terms[:r].sum()
+        assert abs(got - want) <= 1e-5 * (q * np.abs(terms).sum() + np.abs(terms[:r]).sum())
     with pytest.raises(B.DsqError) as e:                      # one element more is refused
         B._check(B.load_library().dsq_soft_quantize_fwd(x.data_ptr(), n + 1, l, u, alpha, bits, y.data_ptr(), None))
     assert e.value.status == 4

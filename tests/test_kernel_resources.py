@@ -30,7 +30,8 @@ def _device_asm(src):
         return open(out).read()
 
 
-@pytest.mark.parametrize("source", ["conv_patch.hip", "conv_simple.hip", "conv_fc.hip", "quantize_act.hip"])
+@pytest.mark.parametrize("source", ["conv_patch_c4r3.hip", "conv_patch_c4r1.hip", "conv_patch_c2r3.hip", "conv_patch_c2r1.hip",
+                                    "conv_simple.hip", "conv_fc.hip", "quantize_act.hip"])
 def test_kernels_stay_inside_their_register_budget(source):
     asm = _device_asm(os.path.join(CSRC, source))
     kernels = re.findall(r"\.name:\s+(\S+).*?\.vgpr_count:\s+(\d+).*?\.vgpr_spill_count:\s+(\d+)", asm, re.S)
