@@ -28,7 +28,6 @@ and the CPU oracle timed on a batch subset of the same stack.
 import argparse
 import json
 import os
-import re
 import sys
 import time
 
@@ -65,18 +64,25 @@ def arithmetic_name(bits):
     return "u%d codes on the int8 MFMA, int32 accumulate, f64 epilogue -> f32" % bits
 
 
-def tracked_traffic(layer_name):
-    """HBM bytes per launch of dsq_conv2d on this layer from the committed
-    rocprofv3 --pmc summary (FETCH_SIZE and WRITE_SIZE runs), or None."""
-    path = os.path.join(ROOT, "profiles", "traffic_conv.md")
+def tracked_traffic(kernel_key, layer_names):
+    """Average HBM bytes per launch of this kernel over these layers, from the
+    committed rocprofv3 --pmc summary (profiles/traffic_config5.md: FETCH_SIZE and
+    WRITE_SIZE runs scaled by a copy kernel of known size), or None if the
+    summary does not cover every one of them.  Rows of that file:
+    | <layer> | <call> | ... | <HBM bytes per launch> |"""
+    path = os.path.join(ROOT, "profiles", "traffic_config5.md")
     if not os.path.exists(path):
         return None, None
-    pat = re.compile(r"^\|\s*%s\s*\|.*?\|\s*(\d+)\s*\|\s*$" % re.escape(layer_name))
+    call = "dsq_quantize_act" if kernel_key.startswith("dsq_quantize_act") else "dsq_conv2d"
+    found = {}
     for line in open(path):
-        m = pat.match(line)
-        if m:
-            return int(m.group(1)), "profiles/traffic_conv.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a copy kernel)"
-    return None, None
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        if len(cells) >= 3 and cells[1] == call and cells[-1].isdigit():
+            found[cells[0]] = int(cells[-1])
+    if not layer_names or any(n not in found for n in layer_names):
+        return None, None
+    return int(sum(found[n] for n in layer_names) / len(layer_names)), \
+        "profiles/traffic_config5.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE per dispatch, scaled by a copy kernel)"
 
 
 def main():
@@ -159,7 +165,19 @@ def main():
     value = 2.0 * macs / step_s / 1e12
 
     # ---- per-kernel average launch durations (each kernel by itself) ---------
-    rows, share = [], []
+    # Launches are grouped by the kernel function they run (dsq_conv2d_plan names the
+    # variant the library picks for a layer; dsq_quantize_act runs one kernel on all of
+    # these tensors); the roofline is that of the group with the largest share of the step.
+    rows, groups = [], {}
+
+    def add(key, launches, seconds, ops, alg_bytes, layer):
+        g = groups.setdefault(key, {"launches": 0, "t": 0.0, "ops": 0.0, "bytes": 0.0, "layers": []})
+        g["launches"] += launches
+        g["t"] += launches * seconds
+        g["ops"] += launches * ops
+        g["bytes"] += launches * alg_bytes
+        g["layers"].append(layer)
+
     for st in states:
         L = st.L
         reps = 3 if len(st.bufs) * LB.LayerState.bytes_per_set(L) > 1e9 else 6
@@ -168,33 +186,41 @@ def main():
         ops = 2.0 * L.macs
         peak = LB.matrix_peak_tops(L.bits)
         bound = "mfma" if ops / st.conv_alg_bytes() >= peak * 1e12 / (HBM_PEAK_GBS * 1e9) else "hbm"
+        plan = B.dsq_conv2d_plan(st.bufs[0].desc)
         rows.append({
             "layer": L.name, "count": L.count, "gemm_MxNxK": [L.N * L.Ho * L.Wo, L.C_out, L.C_in * L.R * L.S],
             "conv_us": round(tc * 1e6, 2), "conv_TOPS": round(ops / tc / 1e12, 1),
             "conv_frac_matrix_peak": round(ops / tc / 1e12 / peak, 4),
             "conv_frac_int8_peak": round(ops / tc / 1e12 / LB.INT8_PEAK_TOPS, 4),
-            "conv_GBps": round(st.conv_alg_bytes() / tc / 1e9, 1), "bound": bound,
+            "conv_GBps": round(st.conv_alg_bytes() / tc / 1e9, 1),
+            "conv_frac_hbm_peak": round(st.conv_alg_bytes() / tc / 1e9 / HBM_PEAK_GBS, 4), "bound": bound,
             "quant_us": round(tq * 1e6, 2), "quant_GBps": round(st.quant_alg_bytes() / tq / 1e9, 1),
+            "quant_frac_hbm_peak": round(st.quant_alg_bytes() / tq / 1e9 / HBM_PEAK_GBS, 4),
+            "conv_kernel": plan,
         })
-        share.append((L.count * tc, st, tc, bound, peak))
-    share.sort(key=lambda t: -t[0])
-    _, dom, dom_t, dom_bound, dom_peak = share[0]
-    dom_ops, dom_bytes = 2.0 * dom.L.macs, dom.conv_alg_bytes()
-    traffic, traffic_source = tracked_traffic(dom.L.name)
+        add("dsq_conv2d, " + plan.split(";")[0], L.count, tc, ops, st.conv_alg_bytes(), L.name)
+        add("dsq_quantize_act (lane-contiguous NHWC kernel)", L.count, tq, 0.0, st.quant_alg_bytes(), L.name)
+    dom_key, dom = max(groups.items(), key=lambda kv: kv[1]["t"])
+    peak = LB.matrix_peak_tops(bits)
+    dom_bound = "mfma" if dom["ops"] / dom["bytes"] >= peak * 1e12 / (HBM_PEAK_GBS * 1e9) else "hbm"
+    traffic, traffic_source = tracked_traffic(dom_key, dom["layers"])
     if dom_bound == "mfma":
-        roofline = {"kernel": "dsq_conv2d on %s" % dom.L.name, "bound": "mfma",
-                    "achieved": round(dom_ops / dom_t / 1e12, 2), "peak": dom_peak, "unit": "TOP/s",
-                    "frac": round(dom_ops / dom_t / 1e12 / dom_peak, 4),
-                    "peak_is": "dense %s matrix peak" % ("FP4" if dom.L.bits <= 2 else "int8"),
-                    "algorithmic_ops_per_launch": int(dom_ops)}
+        roofline = {"kernel": dom_key, "bound": "mfma", "achieved": round(dom["ops"] / dom["t"] / 1e12, 2),
+                    "peak": peak, "unit": "TOP/s", "frac": round(dom["ops"] / dom["t"] / 1e12 / peak, 4),
+                    "peak_is": "dense %s matrix peak" % ("FP4" if bits <= 2 else "int8")}
     else:
-        roofline = {"kernel": "dsq_conv2d on %s" % dom.L.name, "bound": "hbm",
-                    "achieved": round(dom_bytes / dom_t / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": round(dom_bytes / dom_t / 1e9 / HBM_PEAK_GBS, 4),
-                    "algorithmic_bytes_per_launch": int(dom_bytes)}
-    roofline.update({"traffic": traffic, "traffic_source": traffic_source,
-                     "launch_us": round(dom_t * 1e6, 2),
-                     "share_of_step": round(share[0][0] / step_s, 3)})
+        roofline = {"kernel": dom_key, "bound": "hbm", "achieved": round(dom["bytes"] / dom["t"] / 1e9, 1),
+                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(dom["bytes"] / dom["t"] / 1e9 / HBM_PEAK_GBS, 4)}
+    roofline.update({
+        "traffic": traffic, "traffic_source": traffic_source,
+        "launches_per_step": dom["launches"], "avg_launch_us": round(dom["t"] / dom["launches"] * 1e6, 2),
+        "algorithmic_bytes_per_launch": int(dom["bytes"] / dom["launches"]),
+        "algorithmic_ops_per_launch": int(dom["ops"] / dom["launches"]),
+        "layers": dom["layers"], "share_of_step": round(dom["t"] / step_s, 3),
+        "other_kernels": {k: {"share_of_step": round(g["t"] / step_s, 3), "launches_per_step": g["launches"],
+                              "avg_launch_us": round(g["t"] / g["launches"] * 1e6, 2),
+                              "TOPS": round(g["ops"] / g["t"] / 1e12, 1), "GBps": round(g["bytes"] / g["t"] / 1e9, 1)}
+                          for k, g in groups.items() if k != dom_key}})
 
     result = {
         "metric": "effective int-TOPS of b-bit conv2d (2*MACs/s), 1 GPU",
@@ -230,7 +256,7 @@ def main():
         result["chained_step"] = {"ms_per_step": round(ch_s * 1e3, 5), "TOPS": round(2.0 * macs / ch_s / 1e12, 2),
                                   "step": "dsq_conv2d_requant per layer (codes in, codes out)"}
         del g_ch
-    del g_step, step_calls, chained_calls, states, share, dom
+    del g_step, step_calls, chained_calls, states
     torch.cuda.empty_cache()
 
     if not args.no_extras:
@@ -257,7 +283,7 @@ def main():
         import oracle
         # the oracle as it stands on a batch subset of the same stack: quantize + direct
         # convolution of the dequantized doubles, every layer; 2*MACs/s needs no scaling
-        n_sub = args.cpu_batch or {3: 8, 4: 64, 5: 2}[args.config]
+        n_sub = args.cpu_batch or {3: 64, 4: 64, 5: 16}[args.config]
         cpu_t, cpu_macs = 0.0, 0
         for li, L in enumerate(layers):
             Ls, inp = inputs.make_config_layer(args.config, li, bits=args.bits, batch=n_sub)

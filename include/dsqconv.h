@@ -285,6 +285,18 @@ dsq_status dsq_soft_quantize_bwd(const float *x, const float *grad_y, size_t n,
                                  float *grad_x, double *grad_alpha_l_u,
                                  void *hip_stream);
 
+/* ---- dsq_conv2d_plan: which kernel a call would run ------------------------
+ * Writes into `text` (host memory, text_bytes bytes, NUL-terminated, truncated
+ * if need be) a one-line description of the kernel and launch configuration
+ * that dsq_conv2d (chained = 0) or dsq_conv2d_requant (chained != 0) would use
+ * for this descriptor (geometry, bits, flags) and this l_a (a non-zero l_a sends
+ * chained layers to the simple kernel).  Nothing is launched.  For benchmark
+ * reports and tests; returns the status the call itself would return for the
+ * descriptor (DSQ_ERR_UNSUPPORTED if a forced kernel cannot take it).
+ */
+dsq_status dsq_conv2d_plan(const dsq_conv_desc *d, int chained, float l_a,
+                           char *text, size_t text_bytes);
+
 /* Static, NUL-terminated description of a status code. */
 const char *dsq_status_string(dsq_status s);
 

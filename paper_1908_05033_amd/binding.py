@@ -27,7 +27,7 @@ EXPORTS = [
     "dsq_act_packed_bytes", "dsq_wgt_packed_bytes", "dsq_wgt_aux_bytes",
     "dsq_quantize_act", "dsq_pack_weights", "dsq_pack_weights_for", "dsq_conv2d", "dsq_conv2d_requant",
     "dsq_soft_quantize_fwd", "dsq_soft_quantize_bwd",
-    "dsq_status_string",
+    "dsq_conv2d_plan", "dsq_status_string",
 ]
 
 
@@ -78,6 +78,8 @@ def load_library():
     lib.dsq_soft_quantize_fwd.argtypes = [vp, sz, f, f, f, i, vp, vp]
     lib.dsq_soft_quantize_bwd.restype = i
     lib.dsq_soft_quantize_bwd.argtypes = [vp, vp, sz, f, f, f, i, vp, vp, vp]
+    lib.dsq_conv2d_plan.restype = i
+    lib.dsq_conv2d_plan.argtypes = [C.POINTER(dsq_conv_desc), i, f, C.c_char_p, sz]
     lib.dsq_status_string.restype = C.c_char_p
     lib.dsq_status_string.argtypes = [i]
     _lib = lib
@@ -185,6 +187,12 @@ def dsq_soft_quantize_bwd(x, grad_y, l, u, alpha, bits, grad_x, grad_alpha_l_u, 
     _check(load_library().dsq_soft_quantize_bwd(
         _dev_ptr(x, torch.float32), _dev_ptr(grad_y, torch.float32), x.numel(), l, u, alpha, bits,
         _dev_ptr(grad_x, torch.float32), _dev_ptr(grad_alpha_l_u, torch.float64), _stream(stream)))
+
+
+def dsq_conv2d_plan(desc, chained=False, l_a=0.0):
+    buf = C.create_string_buffer(512)
+    _check(load_library().dsq_conv2d_plan(C.byref(desc), int(bool(chained)), l_a, buf, len(buf)))
+    return buf.value.decode()
 
 
 # ---------------------------------------------------------------------------

@@ -77,6 +77,22 @@ def build_library(verbose=False, incremental=False, jobs=None):
     return LIB
 
 
+def build_ceilings_probe():
+    """The stand-alone micro-benchmark of the machine's ceilings (matrix
+    instruction rates, LDS, vector L1, HBM): ceilings/ceilings_probe."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    src = os.path.join(HERE, "ceilings", "ceilings.hip")
+    exe = os.path.join(HERE, "ceilings", "ceilings_probe")
+    proc = subprocess.run([hipcc, "--offload-arch=gfx950", "-O3", "-Xclang", "-target-feature", "-Xclang",
+                           "-packed-fp32-ops", src, "-o", exe],
+                          stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if proc.returncode != 0:
+        raise RuntimeError("hipcc failed on ceilings.hip:\n" + proc.stdout)
+    return exe
+
+
 if __name__ == "__main__":
     import sys
     print(build_library(verbose="-q" not in sys.argv, incremental="-i" in sys.argv))
+    if "-i" not in sys.argv:
+        print(build_ceilings_probe())

@@ -1,6 +1,7 @@
 // C ABI of libdsqconv (see include/dsqconv.h): host-side validation and
 // dispatch only; every step of the path runs in the HIP kernels.
 #include <math.h>
+#include <stdio.h>
 #include <string.h>
 
 #include "../../include/dsqconv.h"
@@ -219,7 +220,42 @@ dsq_status launch_conv(const DsqConvArgs &a, hipStream_t stream)
     return e == hipSuccess ? DSQ_OK : DSQ_ERR_HIP;
 }
 
+// The kernel launch_conv would pick, as text.
+dsq_status describe_conv(const DsqConvArgs &a, char *text, size_t n)
+{
+    const int kernel = a.kernel;
+    if (kernel == 7 || kernel == 0) {
+        const bool fc_ok = kernel == 7 ? dsq_conv_fc_supported(a) : dsq_conv_fc_preferred(a);
+        if (kernel == 7 && !fc_ok) return DSQ_ERR_UNSUPPORTED;
+        if (fc_ok) {
+            snprintf(text, n, "split-K kernel for 1x1 layers with few pixels: container %d%s", dsq_container(a.bits),
+                     a.rq ? ", chained epilogue" : "");
+            return DSQ_OK;
+        }
+    }
+    const int force_tile = kernel >= 3 ? kernel - 3 : -1;
+    if (kernel != 1 && dsq_conv_patch_describe(a, force_tile, text, n)) return DSQ_OK;
+    if (kernel >= 2) return DSQ_ERR_UNSUPPORTED;
+    snprintf(text, n, "simple kernel (one wave per 32x32 tile): container %d%s", dsq_container(a.bits),
+             a.rq ? ", chained epilogue" : "");
+    return DSQ_OK;
+}
+
 }  // namespace
+
+dsq_status dsq_conv2d_plan(const dsq_conv_desc *d, int chained, float l_a, char *text, size_t text_bytes)
+{
+    if (!text || text_bytes == 0) return DSQ_ERR_NULL;
+    text[0] = 0;
+    DsqConvArgs a;
+    // (the pointers only have to pass the checks: nothing is launched)
+    alignas(16) static const char dummy[16] = {0};
+    const dsq_status st = conv_args(d, dummy, (const int32_t *)dummy, l_a, l_a + 1.0f, dummy, dummy, a);
+    if (st != DSQ_OK) return st;
+    a.rq = chained != 0;
+    a.rq_Cp = dsq_round_up(a.C_out, 64);
+    return describe_conv(a, text, text_bytes);
+}
 
 dsq_status dsq_conv2d(const dsq_conv_desc *d, const void *act_packed, const int32_t *pix_code_sum,
                       float l_a, float u_a, const void *w_packed, const void *w_aux, float *out,

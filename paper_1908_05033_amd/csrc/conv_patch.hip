@@ -1,5 +1,7 @@
 // dsq_conv2d, LDS-patch kernel: tile planning and dispatch (host side).  The
 // kernel itself is in conv_patch_kernel.h.
+#include <stdio.h>
+
 #include "conv_patch_kernel.h"
 
 namespace {
@@ -150,6 +152,23 @@ bool dsq_conv_patch_supported(const DsqConvArgs &a, int force_tile)
     int which, ks;
     PatchPlan pl;
     return choose_plan(a, force_tile, which, ks, pl);
+}
+
+int dsq_conv_patch_describe(const DsqConvArgs &a, int force_tile, char *text, size_t n)
+{
+    int which, ks;
+    PatchPlan pl;
+    if (!choose_plan(a, force_tile, which, ks, pl)) return 0;
+    const TileCfg &tc = tile_cfg(which);
+    const int BC = 32 * tc.CT * tc.WC;
+    const int need = (pl.units + 255) / 256;
+    const int upt = need <= 2 ? 2 : need <= 4 ? 4 : need <= 8 ? 8 : 12;
+    const int blocks = pl.tiles_w * pl.row_tiles * ((a.C_out + BC - 1) / BC);
+    snprintf(text, n, "patch kernel: container %d, %dx%d filter, tile %dx%d (pixels x channels), %d wave group%s, "
+             "%d fetch units per thread%s; strip width %d, patch %dx%d, %d workgroups, %d LDS bytes",
+             dsq_container(a.bits), a.R, a.R, 32 * tc.PF * tc.WP, BC, ks, ks == 1 ? "" : "s", upt,
+             a.rq ? ", chained epilogue" : "", pl.TW, pl.PR, pl.PC, blocks, plan_lds_bytes(pl, BC));
+    return 1;
 }
 
 hipError_t dsq_launch_conv_patch(const DsqConvArgs &args, int force_tile, hipStream_t stream)

@@ -92,6 +92,8 @@ hipError_t dsq_launch_conv_simple(const DsqConvArgs &a, hipStream_t stream);
 hipError_t dsq_launch_conv_patch(const DsqConvArgs &a, int force_tile, hipStream_t stream);
 // Whether the LDS-patch kernel supports this geometry with that tile.
 bool dsq_conv_patch_supported(const DsqConvArgs &a, int force_tile);
+// The launch configuration it would use, as text; returns 0 if it does not take the geometry.
+int dsq_conv_patch_describe(const DsqConvArgs &a, int force_tile, char *text, size_t n);
 
 // Split-K kernel for 1x1 layers with few output pixels (fully connected layers).
 bool dsq_conv_fc_supported(const DsqConvArgs &a);   // the kernel takes this layer

@@ -14,9 +14,9 @@ GPU (timing does not depend on the values).  Each call is timed twice:
   cold   launches captured in a hipGraph that rotates over as many buffer sets
          as it takes to exceed 600 MB, so that the 256 MB last-level cache
          cannot serve them (what a layer inside a large network sees);
-  warm   the same graph over two buffer sets only, whose tensors stay in the
-         last-level cache when they fit (what a small layer called in a tight
-         loop sees).
+  warm   a graph of as many launches over two buffer sets only, whose tensors
+         stay in the last-level cache when they fit (what a small layer
+         called in a tight loop sees).
 
 Both are timed with events on the launch stream.  With --chained it also times
 dsq_conv2d_requant (the layer's output written as the next layer's packed
@@ -166,8 +166,10 @@ def bench_layer(L, kernel=0, many_in_flight=False, min_bytes=600e6, reps=5, chai
             if chained:
                 st.conv_chained(b)
         torch.cuda.synchronize()
-    warm = st.bufs[:2]
-    warm_reps = max(reps, reps * sets // 8)
+    # warm: two buffer sets, repeated inside the graph so that a replay holds at least as
+    # many launches as a cold one (the cost of starting a graph is spread the same way)
+    warm = st.bufs[:2] * max(16, sets // 2)
+    warm_reps = reps
     tq = time_graph(st.calls(st.quant), stream, reps)
     tc = time_graph(st.calls(st.conv), stream, reps)
     tq_warm = time_graph(st.calls(st.quant, warm), stream, warm_reps)

@@ -32,5 +32,5 @@ def test_tracked_traffic_reads_the_committed_summary_only():
     spec = importlib.util.spec_from_file_location("bench_module", os.path.join(ROOT, "bench.py"))
     bench = importlib.util.module_from_spec(spec)
     spec.loader.exec_module(bench)
-    value, source = bench.tracked_traffic("no.such.layer")
+    value, source = bench.tracked_traffic("dsq_conv2d, some kernel", ["no.such.layer"])
     assert value is None and source is None
