@@ -336,9 +336,10 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
             // (the loads just issued stay in front of this tap's matrix instructions:
             // left to itself the scheduler sinks each weight load to right before its
             // use, WD taps later, which exposes the full load latency at every tap.  Not
-            // where the patch prefetch holds many registers (the variants then spill), and
+            // where the patch prefetch or the 4-bit 256x128 tile holds many registers (the
+            // variants then spill), and
             // not with two wave groups, where it measured slower)
-            if constexpr (UPT <= 4 && KS == 1) __builtin_amdgcn_sched_barrier(0);
+            if constexpr (UPT <= 4 && KS == 1 && !(CONT == 4 && PF == 4)) __builtin_amdgcn_sched_barrier(0);
             // consecutive MFMAs go to different accumulators
 #pragma unroll
             for (int kh = 0; kh < KH; ++kh)
