@@ -66,6 +66,17 @@
  *       of the 32x32x64 FP4 matrix instruction as they stand; the nibble order
  *       is the one in which a packed 2-bit activation word w spreads into
  *       w & 0x33333333 and (w >> 2) & 0x33333333.
+ *
+ * Dense 3-bit activation codes (DSQ_PACK_DENSE3; Sec. 3.1 gives every quantizer
+ *   its own b, and b = 3 is one of the widths the paper deploys, Sec. 4.5): 3 bits
+ *   per code instead of a 4-bit container.  [N][H][W][Cp/32] units of 12 bytes,
+ *   Cp = C rounded up to 64 (channels >= C hold code 0).  A unit holds channels
+ *   c0..c31 as three words: word 0 / word 1 = the low two bits of channels 0..15 /
+ *   16..31 in the 2-bit container format above, word 2 = the high bits, bit
+ *   8j + g = bit 2 of channel 4g + j (j = 0..3, g = 0..7).  Written by
+ *   dsq_quantize_act_ex and by dsq_conv2d_requant with DSQ_CONV_NEXT_DENSE3, read
+ *   by the convolution calls with DSQ_CONV_ACT_DENSE3; the weights of such a layer
+ *   are packed as for any 3-bit layer (dsq_pack_weights with bits = 3).
  */
 #ifndef DSQCONV_H
 #define DSQCONV_H
@@ -96,6 +107,10 @@ typedef enum {
 
 typedef enum { DSQ_NHWC = 0, DSQ_NCHW = 1 } dsq_layout;
 
+/* How activation codes are packed: in 2- or 4-bit containers (every width), or
+ * 3-bit codes densely (bits = 3 only). */
+typedef enum { DSQ_PACK_CONTAINER = 0, DSQ_PACK_DENSE3 = 1 } dsq_packing;
+
 /* Per-call choices of the convolution entry points, OR-ed into
  * dsq_conv_desc.flags.  0 is the normal value: the library picks the kernel
  * and optimises for the shortest time of a single call on an otherwise idle
@@ -119,10 +134,17 @@ typedef enum { DSQ_NHWC = 0, DSQ_NCHW = 1 } dsq_layout;
  *   one workgroup per compute unit then run with one wave group per workgroup
  *   instead of two, so that workgroups of different calls share the compute
  *   units.  Results are identical bit for bit either way.
+ * DSQ_CONV_ACT_DENSE3: act_packed is in the dense 3-bit format (bits must be 3).
+ *   The split-K kernel does not read that format: fully connected layers then run
+ *   on the implicit-GEMM kernels, and DSQ_CONV_KERNEL(7) gives DSQ_ERR_UNSUPPORTED.
+ * DSQ_CONV_NEXT_DENSE3 (dsq_conv2d_requant only): codes_next is written in the
+ *   dense 3-bit format (bits_next must be 3).
  * Any other bit set gives DSQ_ERR_UNSUPPORTED.
  */
 #define DSQ_CONV_KERNEL(k) ((k) & 15)
 #define DSQ_CONV_MANY_IN_FLIGHT 0x10
+#define DSQ_CONV_ACT_DENSE3 0x20
+#define DSQ_CONV_NEXT_DENSE3 0x40
 
 typedef struct {
     int N, C_in, H, W;   /* input activation */
@@ -136,6 +158,9 @@ typedef struct {
 
 /* Bytes of the packed activation tensor for an N x H x W x C input. */
 size_t dsq_act_packed_bytes(int N, int H, int W, int C, int bits);
+/* The same for a given packing (DSQ_PACK_DENSE3: bits must be 3; 0 otherwise). */
+size_t dsq_act_packed_bytes_ex(int N, int H, int W, int C, int bits,
+                               dsq_packing packing);
 /* Bytes of the packed weight tensor. */
 size_t dsq_wgt_packed_bytes(int C_out, int C_in, int R, int S, int bits);
 /* Bytes of the per-output-channel side table written by dsq_pack_weights:
@@ -155,6 +180,18 @@ dsq_status dsq_quantize_act(const float *x, dsq_layout layout, int N, int C,
                             int H, int W, float l, float u, int bits,
                             void *codes_packed, size_t codes_bytes,
                             int32_t *pix_code_sum, void *hip_stream);
+
+/* ---- dsq_quantize_act_ex: the same with a choice of packing ---------------
+ * packing = DSQ_PACK_CONTAINER is dsq_quantize_act.  DSQ_PACK_DENSE3 (bits = 3,
+ * C rounded up to 64 at most 8192, else DSQ_ERR_UNSUPPORTED) writes the dense
+ * 3-bit format described at the top of this file; codes and pixel sums are the
+ * same numbers in either packing.
+ */
+dsq_status dsq_quantize_act_ex(const float *x, dsq_layout layout, int N, int C,
+                               int H, int W, float l, float u, int bits,
+                               dsq_packing packing, void *codes_packed,
+                               size_t codes_bytes, int32_t *pix_code_sum,
+                               void *hip_stream);
 
 /* ---- dsq_pack_weights: Alg. 1 steps 1 and 3 for the weights ------------
  * w_oihw       device, float32 [C_out][C_in][R][S]; may be NULL if
@@ -239,7 +276,8 @@ dsq_status dsq_conv2d(const dsq_conv_desc *d, const void *act_packed,
  * l_next, u_next, bits_next   clip range and width of the next layer's
  *                   activation quantizer (bits_next may differ from d->bits)
  * codes_next        device, out, dsq_act_packed_bytes(N, Ho, Wo, C_out,
- *                   bits_next) bytes; codes_bytes is the caller's buffer size
+ *                   bits_next) bytes (dsq_act_packed_bytes_ex(.., DSQ_PACK_DENSE3)
+ *                   with DSQ_CONV_NEXT_DENSE3); codes_bytes is the caller's buffer size
  * pix_code_sum_next device, out, int32[N*Ho*Wo]; the call clears it with a fill
  *                   kernel on the same stream (no memset node, so the call can
  *                   be captured into a HIP graph) and accumulates with integer

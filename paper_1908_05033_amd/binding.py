@@ -18,14 +18,17 @@ LIB_PATH = os.path.join(HERE, "libdsqconv.so")
 DSQ_NHWC, DSQ_NCHW = 0, 1
 DSQ_OK = 0
 DSQ_CONV_MANY_IN_FLIGHT = 0x10
+DSQ_CONV_ACT_DENSE3 = 0x20
+DSQ_CONV_NEXT_DENSE3 = 0x40
+DSQ_PACK_CONTAINER, DSQ_PACK_DENSE3 = 0, 1
 
 
 def DSQ_CONV_KERNEL(k):
     return k & 15
 
 EXPORTS = [
-    "dsq_act_packed_bytes", "dsq_wgt_packed_bytes", "dsq_wgt_aux_bytes",
-    "dsq_quantize_act", "dsq_pack_weights", "dsq_pack_weights_for", "dsq_conv2d", "dsq_conv2d_requant",
+    "dsq_act_packed_bytes", "dsq_act_packed_bytes_ex", "dsq_wgt_packed_bytes", "dsq_wgt_aux_bytes",
+    "dsq_quantize_act", "dsq_quantize_act_ex", "dsq_pack_weights", "dsq_pack_weights_for", "dsq_conv2d", "dsq_conv2d_requant",
     "dsq_soft_quantize_fwd", "dsq_soft_quantize_bwd",
     "dsq_conv2d_plan", "dsq_status_string",
 ]
@@ -59,6 +62,10 @@ def load_library():
     vp, sz, i, f = C.c_void_p, C.c_size_t, C.c_int, C.c_float
     lib.dsq_act_packed_bytes.restype = sz
     lib.dsq_act_packed_bytes.argtypes = [i] * 5
+    lib.dsq_act_packed_bytes_ex.restype = sz
+    lib.dsq_act_packed_bytes_ex.argtypes = [i] * 6
+    lib.dsq_quantize_act_ex.restype = i
+    lib.dsq_quantize_act_ex.argtypes = [vp, i, i, i, i, i, f, f, i, i, vp, sz, vp, vp]
     lib.dsq_wgt_packed_bytes.restype = sz
     lib.dsq_wgt_packed_bytes.argtypes = [i] * 5
     lib.dsq_wgt_aux_bytes.restype = sz
@@ -119,6 +126,10 @@ def dsq_act_packed_bytes(N, H, W, C, bits):
     return int(load_library().dsq_act_packed_bytes(N, H, W, C, bits))
 
 
+def dsq_act_packed_bytes_ex(N, H, W, C, bits, packing):
+    return int(load_library().dsq_act_packed_bytes_ex(N, H, W, C, bits, packing))
+
+
 def dsq_wgt_packed_bytes(C_out, C_in, R, S, bits):
     return int(load_library().dsq_wgt_packed_bytes(C_out, C_in, R, S, bits))
 
@@ -130,6 +141,13 @@ def dsq_wgt_aux_bytes(C_out, R, S):
 def dsq_quantize_act(x, layout, N, C, H, W, l, u, bits, codes_packed, pix_code_sum, stream=None):
     _check(load_library().dsq_quantize_act(
         _dev_ptr(x, torch.float32), layout, N, C, H, W, l, u, bits,
+        _dev_ptr(codes_packed, torch.uint8), codes_packed.numel() if codes_packed is not None else 0,
+        _dev_ptr(pix_code_sum, torch.int32), _stream(stream)))
+
+
+def dsq_quantize_act_ex(x, layout, N, C, H, W, l, u, bits, packing, codes_packed, pix_code_sum, stream=None):
+    _check(load_library().dsq_quantize_act_ex(
+        _dev_ptr(x, torch.float32), layout, N, C, H, W, l, u, bits, packing,
         _dev_ptr(codes_packed, torch.uint8), codes_packed.numel() if codes_packed is not None else 0,
         _dev_ptr(pix_code_sum, torch.int32), _stream(stream)))
 

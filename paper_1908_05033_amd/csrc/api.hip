@@ -35,6 +35,13 @@ size_t dsq_act_packed_bytes(int N, int H, int W, int C, int bits)
     return (size_t)N * H * W * (size_t)(dsq_round_up(C, 64) * dsq_container(bits) / 8);
 }
 
+size_t dsq_act_packed_bytes_ex(int N, int H, int W, int C, int bits, dsq_packing packing)
+{
+    if (packing == DSQ_PACK_CONTAINER) return dsq_act_packed_bytes(N, H, W, C, bits);
+    if (packing != DSQ_PACK_DENSE3 || bits != 3 || N <= 0 || H <= 0 || W <= 0 || C <= 0) return 0;
+    return (size_t)N * H * W * (size_t)(dsq_round_up(C, 64) / 32 * 12);
+}
+
 size_t dsq_wgt_packed_bytes(int C_out, int C_in, int R, int S, int bits)
 {
     if (C_out <= 0 || C_in <= 0 || R <= 0 || S <= 0 || !bits_ok(bits)) return 0;
@@ -66,6 +73,31 @@ dsq_status dsq_quantize_act(const float *x, dsq_layout layout, int N, int C, int
     th.inv_delta = 1.0f / ((u - l) / (float)((1 << bits) - 1));
     hipError_t e = dsq_launch_quantize_act(x, layout == DSQ_NCHW, N, C, H, W, l, u, bits, th,
                                            codes_packed, pix_code_sum, (hipStream_t)hip_stream);
+    return e == hipSuccess ? DSQ_OK : DSQ_ERR_HIP;
+}
+
+dsq_status dsq_quantize_act_ex(const float *x, dsq_layout layout, int N, int C, int H, int W, float l, float u,
+                               int bits, dsq_packing packing, void *codes_packed, size_t codes_bytes,
+                               int32_t *pix_code_sum, void *hip_stream)
+{
+    if (packing == DSQ_PACK_CONTAINER)
+        return dsq_quantize_act(x, layout, N, C, H, W, l, u, bits, codes_packed, codes_bytes, pix_code_sum, hip_stream);
+    if (!x || !codes_packed || !pix_code_sum) return DSQ_ERR_NULL;
+    if (!bits_ok(bits)) return DSQ_ERR_BITS;
+    if (packing != DSQ_PACK_DENSE3 || bits != 3) return DSQ_ERR_UNSUPPORTED;
+    if (!range_ok(l, u)) return DSQ_ERR_RANGE;
+    if (N <= 0 || C <= 0 || H <= 0 || W <= 0) return DSQ_ERR_SHAPE;
+    if (layout != DSQ_NHWC && layout != DSQ_NCHW) return DSQ_ERR_UNSUPPORTED;
+    if ((long long)N * H * W * dsq_round_up(C, 64) > kMaxElems) return DSQ_ERR_UNSUPPORTED;
+    if (dsq_round_up(C, 64) > 8192) return DSQ_ERR_UNSUPPORTED;       // (one thread per 32-channel unit of a pixel)
+    if (layout == DSQ_NCHW && N > 65535) return DSQ_ERR_UNSUPPORTED;
+    if (!aligned16(x) || !aligned16(codes_packed) || !aligned16(pix_code_sum)) return DSQ_ERR_ALIGN;
+    if (codes_bytes < dsq_act_packed_bytes_ex(N, H, W, C, bits, packing)) return DSQ_ERR_SIZE;
+    DsqThresholds th;
+    quantizer_thresholds(l, u, bits, th.thr);
+    th.inv_delta = 1.0f / ((u - l) / 7.0f);
+    hipError_t e = dsq_launch_quantize_act_dense3(x, layout == DSQ_NCHW, N, C, H, W, l, u, th, codes_packed,
+                                                  pix_code_sum, (hipStream_t)hip_stream);
     return e == hipSuccess ? DSQ_OK : DSQ_ERR_HIP;
 }
 
@@ -128,13 +160,17 @@ dsq_status conv_args(const dsq_conv_desc *d, const void *act_packed, const int32
     if (9LL * d->R * d->S * Cp > (1LL << 22)) return DSQ_ERR_UNSUPPORTED;
     if ((long long)d->N * Ho * Wo * dsq_round_up(d->C_out, 64) > kMaxElems) return DSQ_ERR_UNSUPPORTED;
     if ((long long)d->N * Ho * Wo + 1024 > kMaxElems) return DSQ_ERR_UNSUPPORTED;
-    if ((d->flags & ~(15 | DSQ_CONV_MANY_IN_FLIGHT)) != 0 || (d->flags & 15) > 7) return DSQ_ERR_UNSUPPORTED;
+    if ((d->flags & ~(15 | DSQ_CONV_MANY_IN_FLIGHT | DSQ_CONV_ACT_DENSE3 | DSQ_CONV_NEXT_DENSE3)) != 0 ||
+        (d->flags & 15) > 7)
+        return DSQ_ERR_UNSUPPORTED;
+    if ((d->flags & DSQ_CONV_ACT_DENSE3) && d->bits != 3) return DSQ_ERR_UNSUPPORTED;
     if (!aligned16(act_packed) || !aligned16(pix_code_sum) || !aligned16(w_packed) || !aligned16(w_aux))
         return DSQ_ERR_ALIGN;
 
     a.N = d->N; a.C_in = d->C_in; a.H = d->H; a.W = d->W; a.C_out = d->C_out; a.R = d->R;
     a.stride = d->stride; a.pad = d->pad; a.bits = d->bits;
     a.Ho = Ho; a.Wo = Wo; a.Cp = Cp; a.Cop = Cop;
+    a.cont = (d->flags & DSQ_CONV_ACT_DENSE3) ? 3 : dsq_container(d->bits);
     a.act = act_packed; a.pix_sum = pix_code_sum; a.l_a = l_a; a.u_a = u_a;
     a.kernel = d->flags & 15;
     a.many_in_flight = (d->flags & DSQ_CONV_MANY_IN_FLIGHT) != 0;
@@ -147,7 +183,7 @@ dsq_status conv_args(const dsq_conv_desc *d, const void *act_packed, const int32
     a.sw_tap = a.sw_total + Cop;
     a.out = nullptr; a.acc = nullptr; a.out_nchw = 0;
     a.rq = 0; a.rq_scale = nullptr; a.rq_shift = nullptr; a.rq_relu = 0;
-    a.rq_l = 0.f; a.rq_u = 1.f; a.rq_bits = 4; a.rq_Cp = 0; a.rq_codes = nullptr; a.rq_pix = nullptr; a.rq_store = 0; a.rq_share = 0;
+    a.rq_l = 0.f; a.rq_u = 1.f; a.rq_bits = 4; a.rq_dense = 0; a.rq_Cp = 0; a.rq_codes = nullptr; a.rq_pix = nullptr; a.rq_store = 0; a.rq_share = 0;
     for (int j = 0; j < 16; ++j) a.rq_thr[j] = 0.f;
     a.rq_inv_delta = 0.f; a.rq_bias = 0.f;
     return DSQ_OK;
@@ -228,7 +264,7 @@ dsq_status describe_conv(const DsqConvArgs &a, char *text, size_t n)
         const bool fc_ok = kernel == 7 ? dsq_conv_fc_supported(a) : dsq_conv_fc_preferred(a);
         if (kernel == 7 && !fc_ok) return DSQ_ERR_UNSUPPORTED;
         if (fc_ok) {
-            snprintf(text, n, "split-K kernel for 1x1 layers with few pixels: container %d%s", dsq_container(a.bits),
+            snprintf(text, n, "split-K kernel for 1x1 layers with few pixels: container %d%s", a.cont,
                      a.rq ? ", chained epilogue" : "");
             return DSQ_OK;
         }
@@ -236,7 +272,7 @@ dsq_status describe_conv(const DsqConvArgs &a, char *text, size_t n)
     const int force_tile = kernel >= 3 ? kernel - 3 : -1;
     if (kernel != 1 && dsq_conv_patch_describe(a, force_tile, text, n)) return DSQ_OK;
     if (kernel >= 2) return DSQ_ERR_UNSUPPORTED;
-    snprintf(text, n, "simple kernel (one wave per 32x32 tile): container %d%s", dsq_container(a.bits),
+    snprintf(text, n, "simple kernel (one wave per 32x32 tile): container %d%s", a.cont,
              a.rq ? ", chained epilogue" : "");
     return DSQ_OK;
 }
@@ -265,6 +301,7 @@ dsq_status dsq_conv2d(const dsq_conv_desc *d, const void *act_packed, const int3
     DsqConvArgs a;
     const dsq_status st = conv_args(d, act_packed, pix_code_sum, l_a, u_a, w_packed, w_aux, a);
     if (st != DSQ_OK) return st;
+    if (d->flags & DSQ_CONV_NEXT_DENSE3) return DSQ_ERR_UNSUPPORTED;     // (only dsq_conv2d_requant writes codes)
     if (out_layout != DSQ_NHWC && out_layout != DSQ_NCHW) return DSQ_ERR_UNSUPPORTED;
     if (!aligned16(out) || (acc_or_null && !aligned16(acc_or_null))) return DSQ_ERR_ALIGN;
     a.out = out; a.acc = acc_or_null; a.out_nchw = out_layout == DSQ_NCHW;
@@ -287,7 +324,12 @@ dsq_status dsq_conv2d_requant(const dsq_conv_desc *d, const void *act_packed,
     if (!aligned16(codes_next) || !aligned16(pix_code_sum_next) || (scale && !aligned16(scale)) ||
         (shift && !aligned16(shift)))
         return DSQ_ERR_ALIGN;
-    if (codes_bytes < dsq_act_packed_bytes(a.N, a.Ho, a.Wo, a.C_out, bits_next)) return DSQ_ERR_SIZE;
+    const bool dense_next = (d->flags & DSQ_CONV_NEXT_DENSE3) != 0;
+    if (dense_next && bits_next != 3) return DSQ_ERR_UNSUPPORTED;
+    if (codes_bytes < dsq_act_packed_bytes_ex(a.N, a.Ho, a.Wo, a.C_out, bits_next,
+                                              dense_next ? DSQ_PACK_DENSE3 : DSQ_PACK_CONTAINER))
+        return DSQ_ERR_SIZE;
+    a.rq_dense = dense_next;
     a.rq = 1; a.rq_scale = scale; a.rq_shift = shift; a.rq_relu = relu != 0;
     a.rq_l = l_next; a.rq_u = u_next; a.rq_bits = bits_next;
     a.rq_Cp = dsq_round_up(a.C_out, 64);

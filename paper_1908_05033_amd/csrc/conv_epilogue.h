@@ -161,7 +161,7 @@ __device__ __forceinline__ uint32_t dsq_requant4_thr(const float (&y)[4], const 
 // lane L (pixel L%32, h = L/32) holds channels o_tile + 8q + 4h + 0..3 for
 // q = 0..3; bytes[q] carries their codes one per byte.  Lanes L and L^32 hold
 // the two halves of every 8-channel word and swap them; the h = 0 lane then
-// stores the 16 (4-bit containers) or 8 (2-bit) bytes of the pixel.  Must be
+// stores the 16 (4-bit containers), 12 (dense 3-bit) or 8 (2-bit) bytes of the pixel.  Must be
 // called by all 64 lanes; `m` < 0 marks a lane without a pixel.  Returns the
 // pixel's code sum over these 32 channels (both lanes of the pair get it).
 __device__ __forceinline__ int dsq_requant_store32(const DsqConvArgs &a, int m, int o_tile, int h,
@@ -173,7 +173,15 @@ __device__ __forceinline__ int dsq_requant_store32(const DsqConvArgs &a, int m, 
     const int total = sum + __shfl_xor(sum, 32);
     if (h == 0 && m >= 0 && o_tile < a.rq_Cp) {
         char *dst = (char *)a.rq_codes;
-        if (dsq_container(a.rq_bits) == 4) {
+        if (a.rq_dense) {
+            // dense 3-bit: the pixel's 32 channels are one 12-byte unit; group 2q is this
+            // lane's bytes[q], group 2q+1 its partner's
+            const uint32_t d[8] = {bytes[0], other[0], bytes[1], other[1], bytes[2], other[2], bytes[3], other[3]};
+            uint32_t l0, l1, hi;
+            dsq_pack32_d3(d, l0, l1, hi);
+            uint32_t *w = reinterpret_cast<uint32_t *>(dst + ((size_t)m * a.rq_Cp + o_tile) / 32 * 12);
+            w[0] = l0; w[1] = l1; w[2] = hi;
+        } else if (dsq_container(a.rq_bits) == 4) {
             // word q = channels 8q..8q+7: byte j = c[j] | c[j+4] << 4
             const v4i w = {(int)(bytes[0] | other[0] << 4), (int)(bytes[1] | other[1] << 4),
                            (int)(bytes[2] | other[2] << 4), (int)(bytes[3] | other[3] << 4)};

@@ -206,6 +206,7 @@ hipError_t launch_fc(const DsqConvArgs &a, hipStream_t stream)
 bool dsq_conv_fc_supported(const DsqConvArgs &a)
 {
     if (a.R != 1 || a.stride != 1 || a.pad != 0) return false;
+    if (a.cont == 3) return false;       // (dense 3-bit input: served by the implicit-GEMM kernels)
     const long long M = (long long)a.N * a.Ho * a.Wo;
     const long long tiles = ((M + 31) / 32) * ((a.C_out + 31) / 32);
     return a.Cp >= 512 && tiles <= 2048;
@@ -225,5 +226,5 @@ bool dsq_conv_fc_preferred(const DsqConvArgs &a)
 
 hipError_t dsq_launch_conv_fc(const DsqConvArgs &a, hipStream_t stream)
 {
-    return dsq_container(a.bits) == 4 ? launch_fc<4>(a, stream) : launch_fc<2>(a, stream);
+    return a.cont == 4 ? launch_fc<4>(a, stream) : launch_fc<2>(a, stream);
 }

@@ -10,8 +10,8 @@ bool plan_patch(const DsqConvArgs &a, int BP, int BC, int PF, int CT, int UPT, i
 {
     // epilogue staging of the four waves (+ the partial sums of a second wave group)
     const int epi_bytes = 4 * KS * (32 * (128 + 16) + PF * 128) + (KS == 2 ? 8 * PF * (CT / 2) * 4096 : 0);
-    const int cont = dsq_container(a.bits);
-    const int UPP = cont == 4 ? 2 : 1;
+    const int cont = a.cont;
+    const int UPP = cont == 2 ? 1 : 2;
     const int NHo = a.N * a.Ho;
     const int Hp = a.H + 2 * a.pad;
     bool found = false;
@@ -105,7 +105,7 @@ int pick_tile(const DsqConvArgs &a)
         // 2-bit layers (FP4 path: the 256x128 tile fits its registers): take that
         // tile when the 128x128 one leaves a nearly empty last round of workgroups
         // (3 per CU, 768 at a time) and the large one (2 per CU, 512) does not
-        if (dsq_container(a.bits) == 2 && !a.rq) {
+        if (a.cont == 2 && !a.rq) {
             const double bm = (double)blocks(kMedium), bl = (double)blocks(kLarge);
             const double waste_m = (double)((blocks(kMedium) + 767) / 768 * 768) / bm;
             const double waste_l = (double)((blocks(kLarge) + 511) / 512 * 512) / bl;
@@ -127,7 +127,7 @@ namespace {
 // the workgroup) only pay when the layer yields about one workgroup per CU.
 bool choose_plan(const DsqConvArgs &a, int force_tile, int &which, int &ks, PatchPlan &pl)
 {
-    if ((long long)a.N * a.H * a.W * (a.Cp * dsq_container(a.bits) / 8) > 0x7FFFFFFFLL) return false;
+    if ((long long)a.N * a.H * a.W * (a.Cp * a.cont / 8) > 0x7FFFFFFFLL) return false;
     which = force_tile >= 0 ? force_tile : pick_tile(a);
     // chained mode: the test-only tile has no variant, and layers with l_a != 0
     // (border-dependent terms) go to the simple kernel
@@ -166,7 +166,7 @@ int dsq_conv_patch_describe(const DsqConvArgs &a, int force_tile, char *text, si
     const int blocks = pl.tiles_w * pl.row_tiles * ((a.C_out + BC - 1) / BC);
     snprintf(text, n, "patch kernel: container %d, %dx%d filter, tile %dx%d (pixels x channels), %d wave group%s, "
              "%d fetch units per thread%s; strip width %d, patch %dx%d, %d workgroups, %d LDS bytes",
-             dsq_container(a.bits), a.R, a.R, 32 * tc.PF * tc.WP, BC, ks, ks == 1 ? "" : "s", upt,
+             a.cont, a.R, a.R, 32 * tc.PF * tc.WP, BC, ks, ks == 1 ? "" : "s", upt,
              a.rq ? ", chained epilogue" : "", pl.TW, pl.PR, pl.PC, blocks, plan_lds_bytes(pl, BC));
     return 1;
 }
@@ -185,12 +185,13 @@ hipError_t dsq_launch_conv_patch(const DsqConvArgs &args, int force_tile, hipStr
         a.rq_store = a.C_out <= 32 * tc.CT * tc.WC;
         a.rq_share = a.rq_store || a.R == 1;
     }
-    const int cont = dsq_container(a.bits);
     const int need = (pl.units + 255) / 256;      // fetch units per thread: instantiated 2, 4, 8, 12
-    switch ((cont == 4 ? 0 : 2) + (a.R == 3 ? 0 : 1)) {
-    case 0: return dsq_conv_patch_c4r3(a, pl, which, ks, need, stream);
-    case 1: return dsq_conv_patch_c4r1(a, pl, which, ks, need, stream);
-    case 2: return dsq_conv_patch_c2r3(a, pl, which, ks, need, stream);
+    switch (2 * a.cont + (a.R == 3 ? 0 : 1)) {
+    case 8: return dsq_conv_patch_c4r3(a, pl, which, ks, need, stream);
+    case 9: return dsq_conv_patch_c4r1(a, pl, which, ks, need, stream);
+    case 6: return dsq_conv_patch_c3r3(a, pl, which, ks, need, stream);
+    case 7: return dsq_conv_patch_c3r1(a, pl, which, ks, need, stream);
+    case 4: return dsq_conv_patch_c2r3(a, pl, which, ks, need, stream);
     default: return dsq_conv_patch_c2r1(a, pl, which, ks, need, stream);
     }
 }

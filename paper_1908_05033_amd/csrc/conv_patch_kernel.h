@@ -94,7 +94,10 @@ template <int CONT, int R, int WP, int WC, int PF, int CT, int UPT, int WD, int 
 __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, OCC))) void conv_patch_kernel(DsqConvArgs a, PatchPlan pl)
 {
     constexpr int T = R * R;
-    constexpr int UPP = CONT == 4 ? 2 : 1;        // 16-byte fetch units per patch pixel
+    // CONT: 2 / 4 = container width of the packed activation codes, 3 = dense 3-bit units
+    // (12 bytes per 32 channels; everything after the patch store is the 4-bit path)
+    constexpr int UPP = CONT == 2 ? 1 : 2;        // fetch units per patch pixel and 64 channels
+    constexpr int UNIT_B = CONT == 3 ? 12 : 16;   // bytes of a fetch unit
     constexpr int KB_BYTES = 64 * CONT / 8;       // packed bytes of 64 channels
     constexpr int WLANE = 16;                     // weight bytes per lane per (tile, cb, tap)
     constexpr bool F4 = CONT == 2;                // 2-bit layers run on the FP4 matrix instruction
@@ -209,7 +212,7 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
             const bool valid = inpatch && n < a.N && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
             const uint32_t pix = valid ? (uint32_t)((n * a.H + ih) * a.W + iw) : 0u;
             src_pix[k] = pix;
-            src_off[k] = pix * row_bytes + half * 16;
+            src_off[k] = pix * row_bytes + half * UNIT_B;
             dst_off[k] = inpatch ? prow * pl.RP + pcol * PIX_STRIDE + half * 32 : dump_off;
             src_valid |= (valid ? 1u : 0u) << k;
             int dp = pl.step_q;
@@ -225,14 +228,28 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
     auto fetch_patch = [&](int cb) {
         const char *base = (const char *)a.act + (size_t)cb * KB_BYTES;
 #pragma unroll
-        for (int k = 0; k < UPT; ++k) pre[k] = *reinterpret_cast<const v4i *>(base + src_off[k]);
+        for (int k = 0; k < UPT; ++k) {
+            if constexpr (CONT == 3) {
+                typedef int v3i __attribute__((ext_vector_type(3)));
+                const v3i t = *reinterpret_cast<const v3i *>(base + src_off[k]);      // (4-byte aligned)
+                pre[k] = (v4i){t.x, t.y, t.z, 0};
+            } else {
+                pre[k] = *reinterpret_cast<const v4i *>(base + src_off[k]);
+            }
+        }
     };
     auto store_units = [&](char *buf, const v4i (&units)[UPT]) {
 #pragma unroll
         for (int k = 0; k < UPT; ++k) {
             const v4i pk = (src_valid >> k & 1) ? units[k] : (v4i){0, 0, 0, 0};
             char *d = buf + dst_off[k];
-            if (CONT == 4) {
+            if (CONT == 3) {
+                // 12 packed bytes = 32 channels -> 32 int8
+                uint32_t g[8];
+                dsq_unpack32_d3((uint32_t)pk.x, (uint32_t)pk.y, (uint32_t)pk.z, g);
+                *reinterpret_cast<v4i *>(d) = (v4i){(int)g[0], (int)g[1], (int)g[2], (int)g[3]};
+                *reinterpret_cast<v4i *>(d + 16) = (v4i){(int)g[4], (int)g[5], (int)g[6], (int)g[7]};
+            } else if (CONT == 4) {
                 // 16 packed bytes = 32 channels -> 32 int8
                 *reinterpret_cast<v4i *>(d) = dsq_unpack16_c4((v2i){pk.x, pk.y});
                 *reinterpret_cast<v4i *>(d + 16) = dsq_unpack16_c4((v2i){pk.z, pk.w});
@@ -339,7 +356,7 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
             // where the patch prefetch or the 4-bit 256x128 tile holds many registers (the
             // variants then spill), and
             // not with two wave groups, where it measured slower)
-            if constexpr (UPT <= 4 && KS == 1 && !(CONT == 4 && PF == 4)) __builtin_amdgcn_sched_barrier(0);
+            if constexpr (UPT <= 4 && KS == 1 && !(CONT >= 3 && PF == 4)) __builtin_amdgcn_sched_barrier(0);
             // consecutive MFMAs go to different accumulators
 #pragma unroll
             for (int kh = 0; kh < KH; ++kh)
@@ -754,3 +771,5 @@ hipError_t dsq_conv_patch_c4r3(const DsqConvArgs &a, const PatchPlan &pl, int wh
 hipError_t dsq_conv_patch_c4r1(const DsqConvArgs &a, const PatchPlan &pl, int which, int ks, int need, hipStream_t stream);
 hipError_t dsq_conv_patch_c2r3(const DsqConvArgs &a, const PatchPlan &pl, int which, int ks, int need, hipStream_t stream);
 hipError_t dsq_conv_patch_c2r1(const DsqConvArgs &a, const PatchPlan &pl, int which, int ks, int need, hipStream_t stream);
+hipError_t dsq_conv_patch_c3r3(const DsqConvArgs &a, const PatchPlan &pl, int which, int ks, int need, hipStream_t stream);
+hipError_t dsq_conv_patch_c3r1(const DsqConvArgs &a, const PatchPlan &pl, int which, int ks, int need, hipStream_t stream);

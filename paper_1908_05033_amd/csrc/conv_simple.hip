@@ -18,7 +18,9 @@ namespace {
 template <int CONT>
 __global__ __launch_bounds__(256) void conv_simple_kernel(DsqConvArgs a)
 {
-    constexpr int WPL = CONT == 4 ? 2 : 1;       // packed words per lane per K half
+    // CONT: 2 / 4 = container width of the packed activation codes, 3 = dense 3-bit units
+    // (the weights of such a layer are in the 4-bit layout)
+    constexpr int WPL = CONT == 2 ? 1 : 2;       // packed weight words per lane per K half
     constexpr int KB_BYTES = 64 * CONT / 8;      // bytes of one pixel's 64-channel block
     constexpr int KG_BYTES = 16 * CONT / 8;      // bytes of 16 channels
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -76,8 +78,17 @@ __global__ __launch_bounds__(256) void conv_simple_kernel(DsqConvArgs a)
             for (int kh = 0; kh < 2; ++kh) {
                 v4i af = {0, 0, 0, 0};
                 if (inside) {
-                    const char *pk = p + (2 * kh + h) * KG_BYTES;   // channels 32*kh + 16*h ..
-                    af = dsq_unpack16_c4(*reinterpret_cast<const v2i *>(pk));
+                    if (CONT == 3) {
+                        // unit kh of the block: its low word h and its high-bit word
+                        const uint32_t *u = reinterpret_cast<const uint32_t *>(p + kh * 12);
+                        const uint32_t low = u[h], hi = u[2];
+                        uint32_t g[8];
+                        dsq_unpack32_d3(low, low, hi >> (4 * h), g);      // groups 4h..4h+3 land in g[0..3]
+                        af = (v4i){(int)g[0], (int)g[1], (int)g[2], (int)g[3]};
+                    } else {
+                        const char *pk = p + (2 * kh + h) * KG_BYTES;   // channels 32*kh + 16*h ..
+                        af = dsq_unpack16_c4(*reinterpret_cast<const v2i *>(pk));
+                    }
                 }
                 const v4i wf = dsq_unpack16_c4(*reinterpret_cast<const v2i *>(wp + kh * WPL));
                 acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf, af, acc, 0, 0, 0);
@@ -109,7 +120,8 @@ hipError_t dsq_launch_conv_simple(const DsqConvArgs &a, hipStream_t stream)
         const hipError_t e = dsq_launch_fill_zero(a.rq_pix, (size_t)M, stream);
         if (e != hipSuccess) return e;
     }
-    if (dsq_container(a.bits) == 4) conv_simple_kernel<4><<<grid, 256, 0, stream>>>(a);
+    if (a.cont == 4) conv_simple_kernel<4><<<grid, 256, 0, stream>>>(a);
+    else if (a.cont == 3) conv_simple_kernel<3><<<grid, 256, 0, stream>>>(a);
     else conv_simple_kernel<2><<<grid, 256, 0, stream>>>(a);
     return hipGetLastError();
 }

@@ -94,6 +94,36 @@ __device__ __forceinline__ v4i dsq_unpack16_c4(v2i p)
     return r;
 }
 
+// ---- dense 3-bit activation codes ---------------------------------------------
+//
+// 32 consecutive channels c0..c31 of a pixel occupy 12 bytes: word 0 / word 1 hold
+// the low two bits of channels 0..15 / 16..31 in the 2-bit container format
+// (byte j = lo(c[j]) | lo(c[j+4]) << 2 | lo(c[j+8]) << 4 | lo(c[j+12]) << 6), word 2
+// the high bits: bit 8j + g = bit 2 of channel 4g + j (j = 0..3, g = 0..7).
+// Group g (channels 4g..4g+3, one code per byte) is therefore
+//   ((low_word >> 2(g%4)) & 0x03030303) | (((high_word >> g) & 0x01010101) << 2).
+
+// The eight groups of one 12-byte unit as int8 words, in channel order.
+__device__ __forceinline__ void dsq_unpack32_d3(uint32_t l0, uint32_t l1, uint32_t hi, uint32_t (&d)[8])
+{
+#pragma unroll
+    for (int g = 0; g < 8; ++g) {
+        const uint32_t low = ((g < 4 ? l0 : l1) >> (2 * (g & 3))) & 0x03030303u;
+        const uint32_t high = (g >= 2 ? hi >> (g - 2) : hi << (2 - g)) & 0x04040404u;
+        d[g] = low | high;
+    }
+}
+
+// The inverse: eight groups (codes < 8, one per byte) -> the three words of a unit.
+__device__ __forceinline__ void dsq_pack32_d3(const uint32_t (&d)[8], uint32_t &l0, uint32_t &l1, uint32_t &hi)
+{
+    l0 = (d[0] & 0x03030303u) | (d[1] & 0x03030303u) << 2 | (d[2] & 0x03030303u) << 4 | (d[3] & 0x03030303u) << 6;
+    l1 = (d[4] & 0x03030303u) | (d[5] & 0x03030303u) << 2 | (d[6] & 0x03030303u) << 4 | (d[7] & 0x03030303u) << 6;
+    hi = 0;
+#pragma unroll
+    for (int g = 0; g < 8; ++g) hi |= ((d[g] >> 2) & 0x01010101u) << g;
+}
+
 // Sum of the four bytes of a word whose bytes are all < 64.
 __device__ __forceinline__ int dsq_bytesum(uint32_t w)
 {

@@ -9,6 +9,8 @@
 struct DsqConvArgs {
     int N, C_in, H, W, C_out, R, stride, pad, bits;
     int Ho, Wo;
+    int cont;      // format of the packed activation codes: 2 or 4 = container width in bits,
+                   // 3 = dense 3-bit units (weights are then in the 4-bit layout)
     int Cp;        // C_in rounded up to 64
     int Cop;       // C_out rounded up to 256
     const void *act;          // packed activation codes
@@ -33,6 +35,7 @@ struct DsqConvArgs {
     int rq_relu;
     float rq_l, rq_u;         // next layer's clip range
     int rq_bits;
+    int rq_dense;             // next layer's codes in the dense 3-bit format (rq_bits == 3)
     // The next layer's quantizer as a step function: rq_thr[j] (j = 1..2^bits-1)
     // is the smallest binary32 value whose code is >= j, found on the host with
     // the very recipe of dsq_code (every step of it is monotone, so
@@ -61,6 +64,10 @@ struct DsqThresholds {
 hipError_t dsq_launch_quantize_act(const float *x, int layout_nchw, int N, int C, int H, int W,
                                    float l, float u, int bits, const DsqThresholds &th, void *codes,
                                    int32_t *pix_sum, hipStream_t stream);
+// The same into the dense 3-bit format (bits == 3, C rounded up to 64 at most 8192).
+hipError_t dsq_launch_quantize_act_dense3(const float *x, int layout_nchw, int N, int C, int H, int W,
+                                          float l, float u, const DsqThresholds &th, void *codes,
+                                          int32_t *pix_sum, hipStream_t stream);
 
 // `cont`: the container (2 or 4 bits) of the layer the weights are for; codes of
 // `bits` <= cont bits are stored in it.

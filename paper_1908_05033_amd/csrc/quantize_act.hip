@@ -166,8 +166,11 @@ __global__ __launch_bounds__(256) void quantize_act_nhwc_coalesced_kernel(
     const float *__restrict__ x, uint32_t *__restrict__ codes, int32_t *__restrict__ pix_sum,
     int total_pixels, int C, int DP, int PB, float inv_qp, float l, float u, int top, DsqThresholds th)
 {
-    constexpr int CPD = 32 / CONT;           // channels per packed word
-    constexpr int LPW = CPD / 4;             // lanes per packed word: 2 or 4
+    // CONT = 3: dense 3-bit output, eight lanes per 12-byte unit of 32 channels (C % 32 == 0)
+    constexpr bool D3 = CONT == 3;
+    constexpr int CPD = D3 ? 32 : 32 / CONT; // channels per packed word (dense: per unit)
+    constexpr int LPW = CPD / 4;             // lanes per packed word: 2 or 4 (dense: 8 per unit)
+    constexpr int WPU = D3 ? 3 : 1;          // words per packed word / unit
     constexpr int MODE = CONT == 2 ? 1 : 2;  // 1- and 2-bit codes: at most three thresholds
     __shared__ int spix[DSQ_QUANT_MAX_PB];
     __shared__ float2 tpairs[16];
@@ -178,7 +181,7 @@ __global__ __launch_bounds__(256) void quantize_act_nhwc_coalesced_kernel(
     const int pixel0 = blockIdx.x * PB;
     const int npix = min(PB, total_pixels - pixel0);
     const int QP = C / 4;                    // float4 units per pixel (a multiple of LPW)
-    const int real_words = C / CPD;          // packed words per pixel that carry channels
+    const int real_words = C / CPD * WPU;    // packed words per pixel that carry channels
     for (int i = tid; i < npix; i += 256) spix[i] = 0;
     __syncthreads();
 
@@ -202,7 +205,24 @@ __global__ __launch_bounds__(256) void quantize_act_nhwc_coalesced_kernel(
         if (q >= QP) { ++p; q -= QP; }
         int s = dsq_bytesum(b);
         uint32_t word;
-        if (CONT == 4) {
+        if (D3) {
+            // lane g of a unit holds group g: its low bits go to word g / 4 at bit 2 (g % 4) of
+            // every byte, its high bits to word 2 at bit g of every byte; the eight lanes OR
+            // their shares together and lanes 0..2 store one word each
+            const int g = tid & 7;
+            const uint32_t low = (b & 0x03030303u) << (2 * (g & 3));
+            uint32_t w0 = g < 4 ? low : 0u, w1 = g < 4 ? 0u : low, w2 = ((b >> 2) & 0x01010101u) << g;
+            w0 |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w0, 0xB1, 0xF, 0xF, true);
+            w1 |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w1, 0xB1, 0xF, 0xF, true);
+            w2 |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w2, 0xB1, 0xF, 0xF, true);
+            w0 |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w0, 0x4E, 0xF, 0xF, true);
+            w1 |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w1, 0x4E, 0xF, 0xF, true);
+            w2 |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w2, 0x4E, 0xF, 0xF, true);
+            w0 |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w0, 0x141, 0xF, 0xF, true);
+            w1 |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w1, 0x141, 0xF, 0xF, true);
+            w2 |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w2, 0x141, 0xF, 0xF, true);
+            word = g == 0 ? w0 : g == 1 ? w1 : w2;
+        } else if (CONT == 4) {
             // word = channels 8w..8w+7: byte j = c[j] | c[j+4] << 4; the odd lane holds c[4..7]
             const uint32_t other = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)b, 0xB1, 0xF, 0xF, true);
             word = b | (other << 4);
@@ -213,7 +233,11 @@ __global__ __launch_bounds__(256) void quantize_act_nhwc_coalesced_kernel(
             v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, true);
             word = v;
         }
-        if (active && (tid & (LPW - 1)) == 0) codes[(size_t)(pixel0 + p) * DP + q / LPW] = word;
+        if (D3) {
+            if (active && (tid & 7) < 3) codes[(size_t)(pixel0 + p) * DP + (q >> 3) * 3 + (tid & 7)] = word;
+        } else if (active && (tid & (LPW - 1)) == 0) {
+            codes[(size_t)(pixel0 + p) * DP + q / LPW] = word;
+        }
         s = dpp_add<0xB1>(s);                                   // lanes ^1
         if (group >= 4) s = dpp_add<0x4E>(s);                   // lanes ^2
         if (group >= 8) s = dpp_add<0x141>(s);                  // other quad (row_half_mirror)
@@ -267,6 +291,92 @@ __global__ __launch_bounds__(256) void quantize_act_nchw_kernel(
     __syncthreads();
     if (wave == 0 && active)
         pix_sum[(size_t)n * HW + hw] = ssum[0][lane] + ssum[1][lane] + ssum[2][lane] + ssum[3][lane];
+}
+
+// ---- dense 3-bit output ---------------------------------------------------------
+// 32 channels of a pixel become one 12-byte unit (format: dsq_device.h).  The recipe
+// itself (dsq_code, IEEE division) runs per element.
+//
+// NHWC: one thread per unit, the units of a pixel in neighbouring lanes; a block owns
+// whole pixels (PB of them, UPX units each) and adds up their code sums in LDS.
+__global__ __launch_bounds__(256) void quantize_act_dense3_nhwc_kernel(const float *__restrict__ x, uint32_t *__restrict__ codes,
+                                                                       int *__restrict__ pix_sum, int pixels, int C, int UPX,
+                                                                       int PB, float l, float u)
+{
+    __shared__ int psum[256];
+    const int tid = threadIdx.x;
+    psum[tid] = 0;
+    __syncthreads();
+    const float delta = dsq_delta(l, u, 7);
+    const int pl = tid / UPX, k = tid - pl * UPX;
+    const long long p = (long long)blockIdx.x * PB + pl;
+    if (pl < PB && p < pixels) {
+        const float *row = x + (size_t)p * C;
+        const bool vec = (C & 3) == 0 && (((uintptr_t)x & 15) == 0);
+        uint32_t d[8];
+        int sum = 0;
+#pragma unroll
+        for (int g = 0; g < 8; ++g) {
+            const int c = 32 * k + 4 * g;
+            float v[4] = {0.f, 0.f, 0.f, 0.f};
+            if (vec && c + 3 < C) {
+                const float4 t = *reinterpret_cast<const float4 *>(row + c);
+                v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (c + j < C) v[j] = row[c + j];
+            }
+            int q[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                q[j] = c + j < C ? dsq_code(v[j], l, u, delta, 7) : 0;       // padding channels: code 0
+                sum += q[j];
+            }
+            d[g] = dsq_bytes4(q[0], q[1], q[2], q[3]);
+        }
+        uint32_t l0, l1, hi;
+        dsq_pack32_d3(d, l0, l1, hi);
+        uint32_t *w = codes + ((size_t)p * UPX + k) * 3;
+        w[0] = l0; w[1] = l1; w[2] = hi;
+        atomicAdd(&psum[pl], sum);
+    }
+    __syncthreads();
+    if (tid < PB && (long long)blockIdx.x * PB + tid < pixels) pix_sum[(long long)blockIdx.x * PB + tid] = psum[tid];
+}
+
+// NCHW: one thread per pixel (neighbouring lanes = neighbouring pixels of a row, so the
+// reads of a channel are contiguous); the thread walks the pixel's units.
+__global__ __launch_bounds__(256) void quantize_act_dense3_nchw_kernel(const float *__restrict__ x, uint32_t *__restrict__ codes,
+                                                                       int *__restrict__ pix_sum, int C, int HW, int UPX,
+                                                                       float l, float u)
+{
+    const int hw = blockIdx.x * 256 + threadIdx.x;
+    const int n = blockIdx.y;
+    if (hw >= HW) return;
+    const float delta = dsq_delta(l, u, 7);
+    const float *img = x + (size_t)n * C * HW + hw;
+    const size_t p = (size_t)n * HW + hw;
+    int sum = 0;
+    for (int k = 0; k < UPX; ++k) {
+        uint32_t d[8];
+#pragma unroll
+        for (int g = 0; g < 8; ++g) {
+            int q[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int c = 32 * k + 4 * g + j;
+                q[j] = c < C ? dsq_code(img[(size_t)c * HW], l, u, delta, 7) : 0;
+                sum += q[j];
+            }
+            d[g] = dsq_bytes4(q[0], q[1], q[2], q[3]);
+        }
+        uint32_t l0, l1, hi;
+        dsq_pack32_d3(d, l0, l1, hi);
+        uint32_t *w = codes + (p * UPX + k) * 3;
+        w[0] = l0; w[1] = l1; w[2] = hi;
+    }
+    pix_sum[p] = sum;
 }
 
 }  // namespace
@@ -336,5 +446,33 @@ hipError_t dsq_launch_quantize_act(const float *x, int layout_nchw, int N, int C
     if (cont == 4) { if (vec) DSQ_Q_LAUNCH(4, true); else DSQ_Q_LAUNCH(4, false); }
     else           { if (vec) DSQ_Q_LAUNCH(2, true); else DSQ_Q_LAUNCH(2, false); }
 #undef DSQ_Q_LAUNCH
+    return hipGetLastError();
+}
+
+hipError_t dsq_launch_quantize_act_dense3(const float *x, int layout_nchw, int N, int C, int H, int W,
+                                          float l, float u, const DsqThresholds &th, void *codes, int32_t *pix_sum,
+                                          hipStream_t stream)
+{
+    const int UPX = dsq_round_up(C, 64) / 32;        // units per pixel (<= 256: checked by the caller)
+    const int pixels = N * H * W;
+    if (layout_nchw) {
+        dim3 grid((H * W + 255) / 256, N);
+        quantize_act_dense3_nchw_kernel<<<grid, 256, 0, stream>>>(x, (uint32_t *)codes, pix_sum, C, H * W, UPX, l, u);
+    } else if (C % 32 == 0 && (((uintptr_t)x & 15) == 0)) {
+        // whole units of real channels: the lane-contiguous kernel (step-function form of the recipe)
+        const int QP = C / 4;
+        const long long total_units = (long long)pixels * QP;
+        int it = 8;
+        while (it > 2 && total_units / (256LL * it) < 2048) it >>= 1;
+        int pb = (256 * it) / QP;
+        if (pb < 1) pb = 1;
+        if (pb > DSQ_QUANT_MAX_PB) pb = DSQ_QUANT_MAX_PB;
+        quantize_act_nhwc_coalesced_kernel<3><<<(pixels + pb - 1) / pb, 256, 0, stream>>>(
+            x, (uint32_t *)codes, pix_sum, pixels, C, UPX * 3, pb, 1.0f / (float)QP, l, u, 7, th);
+    } else {
+        const int PB = 256 / UPX;
+        quantize_act_dense3_nhwc_kernel<<<(pixels + PB - 1) / PB, 256, 0, stream>>>(x, (uint32_t *)codes, pix_sum,
+                                                                                    pixels, C, UPX, PB, l, u);
+    }
     return hipGetLastError();
 }

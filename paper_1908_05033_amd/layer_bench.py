@@ -71,13 +71,17 @@ class LayerState:
     """Device buffers and call closures of one layer over ``sets`` buffer sets.
     Weights are packed once (model-load time)."""
 
-    def __init__(self, L, sets, flags=0, chained=False, u_a=2.5, gen=None, bits_next=None):
+    def __init__(self, L, sets, flags=0, chained=False, u_a=2.5, gen=None, bits_next=None, dense3=False):
         dev = "cuda"
         self.L = L
+        self.dense3 = dense3          # 3-bit layers: dense 3-bit codes in (and out of the chained call)
+        self.packing = B.DSQ_PACK_DENSE3 if dense3 else B.DSQ_PACK_CONTAINER
+        if dense3:
+            flags |= B.DSQ_CONV_ACT_DENSE3
         gen = gen or torch.Generator(device=dev).manual_seed(inputs.BASE_SEED)
         self.in_bytes = L.N * L.H * L.W * L.C_in * 4
         self.out_bytes = L.N * L.Ho * L.Wo * L.C_out * 4
-        self.code_bytes = B.dsq_act_packed_bytes(L.N, L.H, L.W, L.C_in, L.bits)
+        self.code_bytes = B.dsq_act_packed_bytes_ex(L.N, L.H, L.W, L.C_in, L.bits, self.packing)
         self.pix_bytes = L.N * L.H * L.W * 4
         self.w_bytes = B.dsq_wgt_packed_bytes(L.C_out, L.C_in, L.R, L.S, L.bits)
         w = torch.randn((L.C_out, L.C_in, L.R, L.S), device=dev, generator=gen) * math.sqrt(2.0 / (L.C_in * L.R * L.S))
@@ -87,6 +91,11 @@ class LayerState:
         for _ in range(sets):
             b = B.alloc_layer(L.N, L.C_in, L.H, L.W, L.C_out, L.R, L.S, L.stride, L.pad, L.bits, flags=flags)
             b.x = torch.randn((L.N, L.H, L.W, L.C_in), device=dev, generator=gen).abs_()
+            if dense3:
+                b.act_packed = torch.empty(self.code_bytes, dtype=torch.uint8, device=dev)
+            # (the chained call's descriptor: the same, plus the format of the codes it writes)
+            b.desc_chained = B.make_desc(L.N, L.C_in, L.H, L.W, L.C_out, L.R, L.S, L.stride, L.pad, L.bits,
+                                         flags | (B.DSQ_CONV_NEXT_DENSE3 if dense3 else 0))
             self.bufs.append(b)
         self.wp, self.aux = self.bufs[0].w_packed, self.bufs[0].w_aux
         self.l_a, self.u_a = 0.0, float(u_a)
@@ -97,7 +106,7 @@ class LayerState:
             self.scale = torch.rand(L.C_out, device=dev, generator=gen) + 0.5
             self.shift = torch.randn(L.C_out, device=dev, generator=gen) * 0.1
             self.l_n, self.u_n = 0.0, 1.0
-            self.next_bytes = B.dsq_act_packed_bytes(L.N, L.Ho, L.Wo, L.C_out, self.bits_next)
+            self.next_bytes = B.dsq_act_packed_bytes_ex(L.N, L.Ho, L.Wo, L.C_out, self.bits_next, self.packing)
             for b in self.bufs:
                 b.codes_next = torch.empty(self.next_bytes, dtype=torch.uint8, device=dev)
                 b.pix_next = torch.empty(L.N * L.Ho * L.Wo, dtype=torch.int32, device=dev)
@@ -113,23 +122,23 @@ class LayerState:
 
     def quant(self, b):
         L = self.L
-        B.dsq_quantize_act(b.x, B.DSQ_NHWC, L.N, L.C_in, L.H, L.W, self.l_a, self.u_a, L.bits,
-                           b.act_packed, b.pix_code_sum)
+        B.dsq_quantize_act_ex(b.x, B.DSQ_NHWC, L.N, L.C_in, L.H, L.W, self.l_a, self.u_a, L.bits, self.packing,
+                              b.act_packed, b.pix_code_sum)
 
     def conv(self, b):
         B.dsq_conv2d(b.desc, b.act_packed, b.pix_code_sum, self.l_a, self.u_a, self.wp, self.aux, b.out,
                      B.DSQ_NHWC, None)
 
     def conv_chained(self, b):
-        B.dsq_conv2d_requant(b.desc, b.act_packed, b.pix_code_sum, self.l_a, self.u_a, self.wp, self.aux,
+        B.dsq_conv2d_requant(b.desc_chained, b.act_packed, b.pix_code_sum, self.l_a, self.u_a, self.wp, self.aux,
                              self.scale, self.shift, True, self.l_n, self.u_n, self.bits_next,
                              b.codes_next, b.pix_next)
 
     def quant_next(self, b):
         """What the chained call saves: quantizing the fp32 output for the next layer."""
         L = self.L
-        B.dsq_quantize_act(b.out, B.DSQ_NHWC, L.N, L.C_out, L.Ho, L.Wo, self.l_n, self.u_n, self.bits_next,
-                           b.codes_next, b.pix_next)
+        B.dsq_quantize_act_ex(b.out, B.DSQ_NHWC, L.N, L.C_out, L.Ho, L.Wo, self.l_n, self.u_n, self.bits_next,
+                              self.packing, b.codes_next, b.pix_next)
 
     def calls(self, method, bufs=None):
         return [(lambda b=b: method(b)) for b in (bufs if bufs is not None else self.bufs)]
@@ -154,10 +163,10 @@ def cold_sets(L, min_bytes=600e6):
     return int(min(MAX_SETS, max(2, -(-min_bytes // LayerState.bytes_per_set(L)))))
 
 
-def bench_layer(L, kernel=0, many_in_flight=False, min_bytes=600e6, reps=5, chained=False, u_a=2.5):
+def bench_layer(L, kernel=0, many_in_flight=False, min_bytes=600e6, reps=5, chained=False, u_a=2.5, dense3=False):
     sets = cold_sets(L, min_bytes)
     flags = B.DSQ_CONV_KERNEL(kernel) | (B.DSQ_CONV_MANY_IN_FLIGHT if many_in_flight else 0)
-    st = LayerState(L, sets, flags=flags, chained=chained, u_a=u_a)
+    st = LayerState(L, sets, flags=flags, chained=chained, u_a=u_a, dense3=dense3)
     stream = torch.cuda.Stream()
     with torch.cuda.stream(stream):
         for b in st.bufs:
@@ -191,7 +200,7 @@ def bench_layer(L, kernel=0, many_in_flight=False, min_bytes=600e6, reps=5, chai
             "chained_speedup": round((tc + tqn) / tcc, 2), "chained_vs_plain_conv": round(tc / tcc, 2),
         }
     return {**extra, **{
-        "layer": L.name, "bits": L.bits, "count": L.count,
+        "layer": L.name, "bits": L.bits, "count": L.count, "codes": "dense 3-bit" if dense3 else "containers",
         "gemm_MxNxK": [L.N * L.Ho * L.Wo, L.C_out, L.C_in * L.R * L.S],
         "conv_us": round(tc * 1e6, 2), "conv_warm_us": round(tc_warm * 1e6, 2), "conv_TOPS": round(tops, 1),
         "conv_frac_int8_peak": round(tops / INT8_PEAK_TOPS, 4),
@@ -216,6 +225,8 @@ def main():
     ap.add_argument("--kernel", type=int, default=0)
     ap.add_argument("--layer", type=int, default=None)
     ap.add_argument("--chained", action="store_true")
+    ap.add_argument("--dense3", action="store_true",
+                    help="3-bit layers (--bits 3): dense 3-bit activation codes instead of 4-bit containers")
     ap.add_argument("--many-in-flight", action="store_true",
                     help="pass DSQ_CONV_MANY_IN_FLIGHT (the default optimises a single call; kernels are "
                          "timed one at a time here)")
@@ -232,7 +243,7 @@ def main():
         layers = [layers[a.layer]]
     tot_t, tot_macs = 0.0, 0
     for L in layers:
-        r = bench_layer(L, kernel=a.kernel, many_in_flight=a.many_in_flight, chained=a.chained)
+        r = bench_layer(L, kernel=a.kernel, many_in_flight=a.many_in_flight, chained=a.chained, dense3=a.dense3)
         print(json.dumps(r), flush=True)
         tot_t += (r["conv_us"] + r["quant_us"]) * 1e-6 * L.count
         tot_macs += L.macs * L.count

@@ -37,6 +37,37 @@ def unpack_act(packed_u8, N, H, W, C, bits):
     return unpack_words(words, bits)
 
 
+def unpack_act_dense3(packed_u8, N, H, W, C):
+    """Dense 3-bit activation bytes -> codes [N, H, W, Cp] (format: 12-byte units of
+    32 channels; words 0 / 1 = low two bits of channels 0..15 / 16..31 as in the
+    2-bit container format, word 2 bit 8j+g = bit 2 of channel 4g+j)."""
+    Cp = round_up(C, 64)
+    w = packed_u8.view(np.uint32).reshape(N, H, W, Cp // 32, 3)
+    out = np.empty((N, H, W, Cp // 32, 32), dtype=np.uint8)
+    for c in range(32):
+        low_word = w[..., c // 16]
+        k = c % 16
+        low = (low_word >> np.uint32(8 * (k & 3) + 2 * (k >> 2))) & np.uint32(3)
+        g, j = c // 4, c % 4
+        high = (w[..., 2] >> np.uint32(8 * j + g)) & np.uint32(1)
+        out[..., c] = (low | (high << np.uint32(2))).astype(np.uint8)
+    return out.reshape(N, H, W, Cp)
+
+
+def pack_act_dense3(codes_nhwc):
+    """Codes [N, H, W, Cp] (Cp a multiple of 32, values < 8) -> dense 3-bit bytes, by the
+    definition of the format (the inverse of unpack_act_dense3)."""
+    N, H, W, Cp = codes_nhwc.shape
+    c = codes_nhwc.reshape(N, H, W, Cp // 32, 32).astype(np.uint32)
+    w = np.zeros((N, H, W, Cp // 32, 3), dtype=np.uint32)
+    for ch in range(32):
+        k = ch % 16
+        w[..., ch // 16] |= (c[..., ch] & 3) << np.uint32(8 * (k & 3) + 2 * (k >> 2))
+        g, j = ch // 4, ch % 4
+        w[..., 2] |= ((c[..., ch] >> 2) & 1) << np.uint32(8 * j + g)
+    return w.reshape(-1).view(np.uint8)
+
+
 def unpack_weights(packed_u8, C_out, C_in, R, bits):
     """Packed weight bytes -> codes [Cop, Cp, R, R] (OIHW order, padded)."""
     Cp, Cop = round_up(C_in, 64), round_up(C_out, 256)

@@ -176,3 +176,40 @@ def test_soft_quantize_rejects_bad_arguments():
     assert bwd(g=None) == 1 and bwd(s=None) == 1 and bwd(gx=None) == 1
     assert bwd(a=0.7) == 3 and bwd(b=7) == 2 and bwd(n=0) == 4
     assert bwd(s=FAKE + 8) == 6 and bwd(g=FAKE + 4) == 6
+
+
+def test_dense_3bit_sizes_and_argument_checks():
+    lib = B.load_library()
+    assert B.dsq_act_packed_bytes_ex(2, 3, 5, 64, 3, B.DSQ_PACK_DENSE3) == 2 * 3 * 5 * 24
+    assert B.dsq_act_packed_bytes_ex(1, 1, 1, 65, 3, B.DSQ_PACK_DENSE3) == 48          # channels padded to 128
+    assert B.dsq_act_packed_bytes_ex(2, 3, 5, 64, 3, B.DSQ_PACK_CONTAINER) == B.dsq_act_packed_bytes(2, 3, 5, 64, 3)
+    for bits in (1, 2, 4, 0, 9):
+        assert B.dsq_act_packed_bytes_ex(2, 3, 5, 64, bits, B.DSQ_PACK_DENSE3) == 0
+    assert B.dsq_act_packed_bytes_ex(2, 3, 5, 64, 3, 5) == 0
+    q = lambda x=FAKE, bits=3, packing=1, C=64, codes=FAKE, nbytes=1 << 20, pix=FAKE, l=0.0, u=1.0: \
+        lib.dsq_quantize_act_ex(x, 0, 1, C, 4, 4, l, u, bits, packing, codes, nbytes, pix, None)
+    assert q(x=None) == 1 and q(codes=None) == 1 and q(pix=None) == 1
+    assert q(bits=7) == 2 and q(bits=4) == 5 and q(packing=3) == 5
+    assert q(l=1.0, u=0.0) == 3 and q(C=0) == 4 and q(C=8256) == 5
+    assert q(x=FAKE + 4) == 6 and q(nbytes=16 * 24 - 1) == 7
+    assert _c(bits=4, flags=B.DSQ_CONV_ACT_DENSE3) == 5 and _c(bits=3, flags=B.DSQ_CONV_NEXT_DENSE3) == 5
+    assert _c(bits=3, flags=B.DSQ_CONV_ACT_DENSE3, out=FAKE + 4) == 6            # (valid flag: fails later)
+    assert _r(bits=3, flags=B.DSQ_CONV_NEXT_DENSE3, bn=4) == 5
+    assert _r(bits=3, flags=B.DSQ_CONV_NEXT_DENSE3, bn=3, nbytes=16 * 24 - 1) == 7
+
+
+def test_dense_3bit_format_helpers_follow_the_documented_layout():
+    """tests/helpers.py unpacks the dense format for the GPU tests; pin it here on a
+    hand-made unit: channel 0 = 7, channel 5 = 4, channel 17 = 3, channel 31 = 6."""
+    import numpy as np
+    from helpers import pack_act_dense3, unpack_act_dense3
+    codes = np.zeros((1, 1, 1, 64), np.uint8)          # (a pixel is padded to whole 64-channel blocks)
+    codes[0, 0, 0, [0, 5, 17, 31]] = [7, 4, 3, 6]
+    words = pack_act_dense3(codes).view(np.uint32)
+    # low bits: ch 0 -> word 0 byte 0 bits 0-1 (3); ch 5 = 4 -> low 0; ch 17 -> word 1, k = 1: byte 1 bits 0-1 (3);
+    # ch 31 -> word 1, k = 15: byte 3 bits 6-7 (2)
+    assert words[0] == 0x00000003 and words[1] == (3 << 8) | (2 << 30)
+    # high bits: bit 8j + g with g = ch // 4, j = ch % 4: ch 0 -> bit 0; ch 5 -> bit 9; ch 31 -> bit 31
+    assert words[2] == (1 << 0) | (1 << 9) | (1 << 31)
+    assert not words[3:].any()
+    assert np.array_equal(unpack_act_dense3(words.view(np.uint8), 1, 1, 1, 64), codes)
