@@ -293,6 +293,28 @@ dsq_status dsq_conv2d_requant(const dsq_conv_desc *d, const void *act_packed,
                               void *codes_next, size_t codes_bytes,
                               int32_t *pix_code_sum_next, void *hip_stream);
 
+/* ---- dsq_conv2d_wq: quantized weights, full-precision activations -----------
+ * The "b/32" rows of the paper's Tables 3, 6 and 7 (e.g. 1-bit weights and
+ * 32-bit activations): Algorithm 1 with the activation quantizer left out, so
+ * that step 5 convolves the dequantized weights w_hat = l_w + Dw*code (step 4)
+ * with the activations themselves.  There is no integer path: levels and
+ * activations are binary32, products are exact inside the fp32 matrix
+ * instruction and sums are accumulated in binary32, so an output differs from
+ * the real-valued convolution by at most about (K + 2) * 2^-24 of the sum of
+ * the absolute values of its K = R*S*C_in products (typically far less).
+ *
+ * d            geometry; bits is the weights' width (1..4); flags must be 0
+ * x            device, float32, N*C_in*H*W elements in x_layout; padding is
+ *              the real number 0
+ * w_packed, w_aux   outputs of dsq_pack_weights_for(.., bits_w = d->bits,
+ *              bits_act = 4, ..): the weight codes in 4-bit fields
+ * out          device, float32, N*Ho*Wo*C_out elements in out_layout
+ */
+dsq_status dsq_conv2d_wq(const dsq_conv_desc *d, const float *x,
+                         dsq_layout x_layout, const void *w_packed,
+                         const void *w_aux, float *out, dsq_layout out_layout,
+                         void *hip_stream);
+
 /* ---- training mode: the differentiable soft quantization function ---------
  * Sec. 3.2: inside interval P_i = [l + i*Delta, l + (i+1)*Delta)
  *     phi(x) = s * tanh(k * (x - m_i)),  m_i = l + (i + 0.5)*Delta

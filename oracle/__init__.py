@@ -163,6 +163,22 @@ def conv_real(a_code, la, ua, w_code, lw, uw, bits, stride, pad):
     return out
 
 
+def conv_weight_only(x, w_code, lw, uw, bits, stride, pad):
+    """A layer whose weights are quantized and whose activations are not (the
+    "b/32" rows of the paper's Tables 3, 6 and 7): Algorithm 1 with the
+    activation quantizer left out.  Step 4 for the weights (levels in float64),
+    step 5 with the float32 activations taken as they are (as float64), summed
+    in float64 and rounded once -> float32 [N, C_out, Ho, Wo].  Also returns the
+    same convolution of the absolute values (the scale a binary32 accumulation
+    error is measured against), in float64 precision rounded to float32."""
+    x = _arr(x, np.float32)
+    w = _arr(w_code, np.uint8)
+    lw, uw = _arr(lw, np.float32), _arr(uw, np.float32)
+    w_hat = np.stack([dequantize(w[o], float(lw[o]), float(uw[o]), bits) for o in range(w.shape[0])])
+    x64 = x.astype(np.float64)
+    return conv_dequantized(x64, w_hat, stride, pad), conv_dequantized(np.abs(x64), np.abs(w_hat), stride, pad)
+
+
 def conv_at(a_code, la, ua, w_code, lw, uw, bits, stride, pad, flat_idx):
     """Sampled outputs: (float32 values, int32 accumulators) at flat indices
     into the N x C_out x Ho x Wo output."""

@@ -28,7 +28,7 @@ def DSQ_CONV_KERNEL(k):
 
 EXPORTS = [
     "dsq_act_packed_bytes", "dsq_act_packed_bytes_ex", "dsq_wgt_packed_bytes", "dsq_wgt_aux_bytes",
-    "dsq_quantize_act", "dsq_quantize_act_ex", "dsq_pack_weights", "dsq_pack_weights_for", "dsq_conv2d", "dsq_conv2d_requant",
+    "dsq_quantize_act", "dsq_quantize_act_ex", "dsq_pack_weights", "dsq_pack_weights_for", "dsq_conv2d", "dsq_conv2d_requant", "dsq_conv2d_wq",
     "dsq_soft_quantize_fwd", "dsq_soft_quantize_bwd",
     "dsq_conv2d_plan", "dsq_status_string",
 ]
@@ -81,6 +81,8 @@ def load_library():
     lib.dsq_conv2d_requant.restype = i
     lib.dsq_conv2d_requant.argtypes = [C.POINTER(dsq_conv_desc), vp, vp, f, f, vp, vp, vp, vp, i, f, f, i,
                                        vp, sz, vp, vp]
+    lib.dsq_conv2d_wq.restype = i
+    lib.dsq_conv2d_wq.argtypes = [C.POINTER(dsq_conv_desc), vp, i, vp, vp, vp, i, vp]
     lib.dsq_soft_quantize_fwd.restype = i
     lib.dsq_soft_quantize_fwd.argtypes = [vp, sz, f, f, f, i, vp, vp]
     lib.dsq_soft_quantize_bwd.restype = i
@@ -194,6 +196,13 @@ def dsq_conv2d_requant(desc, act_packed, pix_code_sum, l_a, u_a, w_packed, w_aux
         l_next, u_next, bits_next,
         _dev_ptr(codes_next, torch.uint8), codes_next.numel() if codes_next is not None else 0,
         _dev_ptr(pix_code_sum_next, torch.int32), _stream(stream)))
+
+
+def dsq_conv2d_wq(desc, x, x_layout, w_packed, w_aux, out, out_layout, stream=None):
+    _check(load_library().dsq_conv2d_wq(
+        C.byref(desc) if desc is not None else None, _dev_ptr(x, torch.float32), x_layout,
+        _dev_ptr(w_packed, torch.uint8), _dev_ptr(w_aux, torch.uint8), _dev_ptr(out, torch.float32), out_layout,
+        _stream(stream)))
 
 
 def dsq_soft_quantize_fwd(x, l, u, alpha, bits, y, stream=None):

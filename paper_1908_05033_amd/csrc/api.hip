@@ -308,6 +308,25 @@ dsq_status dsq_conv2d(const dsq_conv_desc *d, const void *act_packed, const int3
     return launch_conv(a, (hipStream_t)hip_stream);
 }
 
+dsq_status dsq_conv2d_wq(const dsq_conv_desc *d, const float *x, dsq_layout x_layout, const void *w_packed,
+                         const void *w_aux, float *out, dsq_layout out_layout, void *hip_stream)
+{
+    if (!x || !out) return DSQ_ERR_NULL;
+    if (d && d->flags != 0) return DSQ_ERR_UNSUPPORTED;
+    DsqConvArgs a;
+    // (geometry and pointer checks shared with the other convolution calls: x stands in
+    // for the two activation-side pointers, the clip range is not used)
+    const dsq_status st = conv_args(d, x, (const int32_t *)x, 0.0f, 1.0f, w_packed, w_aux, a);
+    if (st != DSQ_OK) return st;
+    if ((x_layout != DSQ_NHWC && x_layout != DSQ_NCHW) || (out_layout != DSQ_NHWC && out_layout != DSQ_NCHW))
+        return DSQ_ERR_UNSUPPORTED;
+    if ((long long)d->N * d->H * d->W * d->C_in > kMaxElems) return DSQ_ERR_UNSUPPORTED;
+    if (!aligned16(out)) return DSQ_ERR_ALIGN;
+    a.out = out; a.out_nchw = out_layout == DSQ_NCHW;
+    const hipError_t e = dsq_launch_conv_wq(a, x, x_layout == DSQ_NCHW, (hipStream_t)hip_stream);
+    return e == hipSuccess ? DSQ_OK : DSQ_ERR_HIP;
+}
+
 dsq_status dsq_conv2d_requant(const dsq_conv_desc *d, const void *act_packed,
                               const int32_t *pix_code_sum, float l_a, float u_a,
                               const void *w_packed, const void *w_aux, const float *scale,

@@ -106,3 +106,7 @@ int dsq_conv_patch_describe(const DsqConvArgs &a, int force_tile, char *text, si
 bool dsq_conv_fc_supported(const DsqConvArgs &a);   // the kernel takes this layer
 bool dsq_conv_fc_preferred(const DsqConvArgs &a);   // ... and is the faster choice for it
 hipError_t dsq_launch_conv_fc(const DsqConvArgs &a, hipStream_t stream);
+
+// Weight-only quantized layer: binary32 activations x (NHWC or NCHW), weights in the
+// packed 4-bit layout; uses the geometry, wq, delta_w, l_w, out and out_nchw of `a`.
+hipError_t dsq_launch_conv_wq(const DsqConvArgs &a, const float *x, int x_nchw, hipStream_t stream);

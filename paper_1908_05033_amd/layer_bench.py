@@ -216,6 +216,37 @@ def bench_layer(L, kernel=0, many_in_flight=False, min_bytes=600e6, reps=5, chai
     }}
 
 
+FP32_MATRIX_PEAK_TFLOPS = 157.3
+
+
+def bench_weight_only(L, bits_w=1, reps=3):
+    """dsq_conv2d_wq (b-bit weights, binary32 activations) on one layer shape: cold timing."""
+    dev = "cuda"
+    gen = torch.Generator(device=dev).manual_seed(inputs.BASE_SEED)
+    per_set = L.N * L.H * L.W * L.C_in * 4 + L.N * L.Ho * L.Wo * L.C_out * 4
+    sets = int(min(MAX_SETS, max(2, -(-600e6 // per_set))))
+    w = torch.randn((L.C_out, L.C_in, L.R, L.S), device=dev, generator=gen) * math.sqrt(2.0 / (L.C_in * L.R * L.S))
+    wf = w.reshape(L.C_out, -1)
+    lw, uw = wf.amin(dim=1).contiguous(), wf.amax(dim=1).contiguous()
+    wp = torch.empty(B.dsq_wgt_packed_bytes(L.C_out, L.C_in, L.R, L.S, 4), dtype=torch.uint8, device=dev)
+    aux = torch.empty(B.dsq_wgt_aux_bytes(L.C_out, L.R, L.S), dtype=torch.uint8, device=dev)
+    B.dsq_pack_weights_for(w, lw, uw, None, L.C_out, L.C_in, L.R, L.S, bits_w, 4, wp, aux)
+    d = B.make_desc(L.N, L.C_in, L.H, L.W, L.C_out, L.R, L.S, L.stride, L.pad, bits_w)
+    xs = [torch.randn((L.N, L.H, L.W, L.C_in), device=dev, generator=gen) for _ in range(sets)]
+    outs = [torch.empty((L.N, L.Ho, L.Wo, L.C_out), device=dev) for _ in range(sets)]
+    stream = torch.cuda.Stream()
+    calls = [(lambda x=x, o=o: B.dsq_conv2d_wq(d, x, B.DSQ_NHWC, wp, aux, o, B.DSQ_NHWC)) for x, o in zip(xs, outs)]
+    with torch.cuda.stream(stream):
+        for fn in calls:
+            fn()
+        torch.cuda.synchronize()
+    t = time_graph(calls, stream, reps)
+    tf = 2.0 * L.macs / t / 1e12
+    return {"layer": L.name, "weight_bits": bits_w, "activations": "binary32", "conv_us": round(t * 1e6, 2),
+            "TFLOPs": round(tf, 1), "frac_fp32_matrix_peak": round(tf / FP32_MATRIX_PEAK_TFLOPS, 4),
+            "GBps": round(per_set / t / 1e9, 1), "buffer_sets": sets}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--cfg", type=int, default=None)
@@ -227,6 +258,8 @@ def main():
     ap.add_argument("--chained", action="store_true")
     ap.add_argument("--dense3", action="store_true",
                     help="3-bit layers (--bits 3): dense 3-bit activation codes instead of 4-bit containers")
+    ap.add_argument("--weight-only", type=int, default=0, metavar="BITS",
+                    help="time dsq_conv2d_wq (BITS-bit weights, binary32 activations) on the config's shapes instead")
     ap.add_argument("--many-in-flight", action="store_true",
                     help="pass DSQ_CONV_MANY_IN_FLIGHT (the default optimises a single call; kernels are "
                          "timed one at a time here)")
@@ -241,6 +274,10 @@ def main():
         layers = inputs.config_layers(a.cfg, a.bits)
     if a.layer is not None:
         layers = [layers[a.layer]]
+    if a.weight_only:
+        for L in layers:
+            print(json.dumps(bench_weight_only(L, a.weight_only)), flush=True)
+        return
     tot_t, tot_macs = 0.0, 0
     for L in layers:
         r = bench_layer(L, kernel=a.kernel, many_in_flight=a.many_in_flight, chained=a.chained, dense3=a.dense3)

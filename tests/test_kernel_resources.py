@@ -31,6 +31,7 @@ def _device_asm(src):
 
 
 @pytest.mark.parametrize("source", ["conv_patch_c4r3.hip", "conv_patch_c4r1.hip", "conv_patch_c2r3.hip", "conv_patch_c2r1.hip",
+                                    "conv_patch_c3r3.hip", "conv_patch_c3r1.hip",
                                     "conv_simple.hip", "conv_fc.hip", "quantize_act.hip"])
 def test_kernels_stay_inside_their_register_budget(source):
     asm = _device_asm(os.path.join(CSRC, source))

@@ -363,3 +363,45 @@ def test_requantize_is_nearest_level_of_the_mapped_value():
         if abs((t % 1) - Fraction(1, 2)) < Fraction(1, 1000):
             continue                                             # too close to a midpoint for this check
         assert got[idx] == int(t + Fraction(1, 2)), idx
+
+
+# ---- weight-only quantized layers (quantized weights, real-valued activations) -----
+
+def test_weight_only_layer_is_the_float_convolution_with_the_weight_levels():
+    """oracle.conv_weight_only against torch's float64 conv2d on separately formed
+    levels, asymmetric geometry, stride 2, padding."""
+    import torch
+    import torch.nn.functional as F
+    rng = np.random.default_rng(11)
+    x = rng.standard_normal((2, 5, 7, 6)).astype(np.float32)
+    w = (rng.standard_normal((4, 5, 3, 3)) * 0.2).astype(np.float32)
+    lw = w.reshape(4, -1).min(axis=1) * np.float32(0.9)
+    uw = w.reshape(4, -1).max(axis=1) * np.float32(0.8)
+    for bits in (1, 2, 3):
+        code = oracle.quantize_weights(w, lw, uw, bits)
+        got, scale = oracle.conv_weight_only(x, code, lw, uw, bits, 2, 1)
+        top = 2 ** bits - 1
+        delta = ((uw.astype(np.float32) - lw.astype(np.float32)) / np.float32(top)).astype(np.float32)
+        levels = lw.astype(np.float64)[:, None, None, None] + delta.astype(np.float64)[:, None, None, None] * code
+        want = F.conv2d(torch.from_numpy(x).double(), torch.from_numpy(levels), stride=2, padding=1).numpy()
+        assert np.abs(got - want).max() <= 1e-6 * np.abs(want).max()
+        want_abs = F.conv2d(torch.from_numpy(np.abs(x)).double(), torch.from_numpy(np.abs(levels)), stride=2, padding=1).numpy()
+        assert np.abs(scale - want_abs).max() <= 1e-6 * want_abs.max()
+        assert (scale >= np.abs(got) * (1 - 1e-6)).all()
+
+
+def test_binary_weights_with_symmetric_range_are_scaled_signs():
+    """1-bit weights with (l, u) = (-alpha, +alpha): the layer is alpha times the
+    convolution with sgn(w) (Sec. 3.1 binary quantizer, sgn(0) = +1)."""
+    import torch
+    import torch.nn.functional as F
+    rng = np.random.default_rng(12)
+    x = rng.standard_normal((1, 6, 5, 5)).astype(np.float32)
+    w = rng.standard_normal((3, 6, 3, 3)).astype(np.float32)
+    w[0, 0, 0, 0] = 0.0
+    alpha = np.array([0.5, 0.25, 2.0], np.float32)
+    code = oracle.quantize_weights(w, -alpha, alpha, 1)
+    got, _ = oracle.conv_weight_only(x, code, -alpha, alpha, 1, 1, 1)
+    sgn = np.where(w >= 0, 1.0, -1.0)
+    want = F.conv2d(torch.from_numpy(x).double(), torch.from_numpy(sgn), padding=1).numpy() * alpha[None, :, None, None]
+    assert np.array_equal(got, want.astype(np.float32))
