@@ -48,6 +48,82 @@ __global__ __launch_bounds__(256) void mfma_fp4(int iters, float *out)
     out[blockIdx.x * 256 + threadIdx.x] = s;
 }
 
+// The same two loops with operands that look like real code tensors: four different
+// pseudo-random operand pairs per wave, used in turn (constant operands keep the
+// datapath quiet; real data toggles it, which shows in the sustained clock).
+__device__ __forceinline__ uint32_t mix(uint32_t x)
+{
+    x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
+    return x;
+}
+__global__ __launch_bounds__(256) void mfma_i8_data(int iters, int *out)
+{
+    v4i a[4], b[4];
+    for (int k = 0; k < 4; ++k)
+        for (int j = 0; j < 4; ++j) {
+            a[k][j] = (int)(mix(threadIdx.x * 64 + blockIdx.x * 7919 + k * 8 + j) & 0x0F0F0F0Fu);       // 4-bit codes as int8
+            b[k][j] = (int)(mix(threadIdx.x * 64 + blockIdx.x * 104729 + k * 8 + j + 4) & 0x0F0F0F0Fu);
+        }
+    v16i acc[4];
+    for (int i = 0; i < 4; ++i) for (int j = 0; j < 16; ++j) acc[i][j] = 0;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[(i + it) & 3], acc[i], 0, 0, 0);
+    }
+    int s = 0;
+    for (int i = 0; i < 4; ++i) for (int j = 0; j < 16; ++j) s += acc[i][j];
+    out[blockIdx.x * 256 + threadIdx.x] = s;
+}
+__global__ __launch_bounds__(256) void mfma_fp4_data(int iters, float *out)
+{
+    v8i a[4], b[4];
+    for (int k = 0; k < 4; ++k) {
+        for (int j = 0; j < 4; ++j) {
+            a[k][j] = (int)(mix(threadIdx.x * 64 + blockIdx.x * 7919 + k * 8 + j) & 0x33333333u);       // 2-bit codes as FP4
+            b[k][j] = (int)(mix(threadIdx.x * 64 + blockIdx.x * 104729 + k * 8 + j + 4) & 0x33333333u);
+        }
+        for (int j = 4; j < 8; ++j) { a[k][j] = 0; b[k][j] = 0; }
+    }
+    v16f acc[4];
+    for (int i = 0; i < 4; ++i) for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            acc[i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[i], b[(i + it) & 3], acc[i], 4, 4, 0, 0, 0, 0);
+        if ((it & 1023) == 1023)                 // (keep the sums finite and exact: start again now and then)
+            for (int i = 0; i < 4; ++i) for (int j = 0; j < 16; ++j) acc[i][j] = acc[i][j] * 0.0f;
+    }
+    float s = 0;
+    for (int i = 0; i < 4; ++i) for (int j = 0; j < 16; ++j) s += acc[i][j];
+    out[blockIdx.x * 256 + threadIdx.x] = s;
+}
+
+// FP6 (e2m3) operands, 32 random six-bit fields (24 bytes) per lane: the form a 3/4-bit
+// layer could run on instead of int8 (a 4-bit code zero-extended to six bits is code/8).
+__global__ __launch_bounds__(256) void mfma_fp6_data(int iters, float *out)
+{
+    v8i a[4], b[4];
+    for (int k = 0; k < 4; ++k) {
+        for (int j = 0; j < 6; ++j) {
+            a[k][j] = (int)mix(threadIdx.x * 64 + blockIdx.x * 7919 + k * 8 + j);            // (e2m3 has no inf or NaN:
+            b[k][j] = (int)mix(threadIdx.x * 64 + blockIdx.x * 104729 + k * 8 + j + 4);      //  every pattern is a number <= 7.5)
+        }
+        a[k][6] = a[k][7] = b[k][6] = b[k][7] = 0;
+    }
+    v16f acc[4];
+    for (int i = 0; i < 4; ++i) for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            acc[i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[i], b[(i + it) & 3], acc[i], 2, 2, 0, 0, 0, 0);
+        if ((it & 255) == 255)
+            for (int i = 0; i < 4; ++i) for (int j = 0; j < 16; ++j) acc[i][j] = acc[i][j] * 0.0f;
+    }
+    float s = 0;
+    for (int i = 0; i < 4; ++i) for (int j = 0; j < 16; ++j) s += acc[i][j];
+    out[blockIdx.x * 256 + threadIdx.x] = s;
+}
+
 // LDS: every lane reads 16 bytes per instruction, 32 pixels `stride` bytes apart per half wave
 __global__ __launch_bounds__(256) void lds_read(int iters, int stride, int *out)
 {
@@ -136,6 +212,26 @@ int main()
         double t = timed([&] { mfma_fp4<4><<<blocks, 256>>>(iters, (float *)out); }, 3);
         double tops = 4.0 * 4 * 2 * 32 * 32 * 64 * blocks * iters / t / 1e12;
         printf("| v_mfma_f32_32x32x64_f8f6f4 (FP4 operands), 4 accumulators, %d workgroups | %.0f TOP/s | 10100 | %.3f |\n", blocks, tops, tops / 10100);
+    }
+    // sustained rates: the same loops ten times longer (tens of milliseconds: clocks settle under load)
+    for (int blocks : {512, 768}) {
+        double t = timed([&] { mfma_i8<4><<<blocks, 256>>>(10 * iters, out); }, 3);
+        double tops = 4.0 * 4 * 2 * 32 * 32 * 32 * blocks * 10.0 * iters / t / 1e12;
+        printf("| v_mfma_i32_32x32x32_i8 sustained (%.0f ms per launch), %d workgroups | %.0f TOP/s | 5000 | %.3f |\n", t * 1e3, blocks, tops, tops / 5000);
+        t = timed([&] { mfma_fp4<4><<<blocks, 256>>>(10 * iters, (float *)out); }, 3);
+        tops = 4.0 * 4 * 2 * 32 * 32 * 64 * blocks * 10.0 * iters / t / 1e12;
+        printf("| v_mfma_f32_32x32x64_f8f6f4 (FP4) sustained (%.0f ms per launch), %d workgroups | %.0f TOP/s | 10100 | %.3f |\n", t * 1e3, blocks, tops, tops / 10100);
+    }
+    for (int blocks : {512, 768}) {
+        double t = timed([&] { mfma_i8_data<<<blocks, 256>>>(10 * iters, out); }, 3);
+        double tops = 4.0 * 4 * 2 * 32 * 32 * 32 * blocks * 10.0 * iters / t / 1e12;
+        printf("| v_mfma_i32_32x32x32_i8 sustained on random 4-bit codes, %d workgroups | %.0f TOP/s | 5000 | %.3f |\n", blocks, tops, tops / 5000);
+        t = timed([&] { mfma_fp4_data<<<blocks, 256>>>(10 * iters, (float *)out); }, 3);
+        tops = 4.0 * 4 * 2 * 32 * 32 * 64 * blocks * 10.0 * iters / t / 1e12;
+        printf("| v_mfma_f32_32x32x64_f8f6f4 (FP4) sustained on random 2-bit codes, %d workgroups | %.0f TOP/s | 10100 | %.3f |\n", blocks, tops, tops / 10100);
+        t = timed([&] { mfma_fp6_data<<<blocks, 256>>>(10 * iters, (float *)out); }, 3);
+        tops = 4.0 * 4 * 2 * 32 * 32 * 64 * blocks * 10.0 * iters / t / 1e12;
+        printf("| v_mfma_f32_32x32x64_f8f6f4 (FP6) sustained on random bit patterns, %d workgroups | %.0f TOP/s | 10100 | %.3f |\n", blocks, tops, tops / 10100);
     }
     {
         double t = timed([&] { mfma_i8<1><<<512, 256>>>(iters, out); }, 3);

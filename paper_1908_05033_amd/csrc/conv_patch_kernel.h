@@ -80,6 +80,16 @@ __device__ __forceinline__ int idiv(int x, int d, uint32_t m, int &rem)
     return q;
 }
 
+// The kernel's first argument where it lives: in the kernel-argument segment.
+__device__ __forceinline__ const DsqConvArgs &kernarg_conv_args()
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    return *reinterpret_cast<const DsqConvArgs *>(__builtin_amdgcn_kernarg_segment_ptr());
+#else
+    return *static_cast<const DsqConvArgs *>(nullptr);      // (host pass of the compiler: never executed)
+#endif
+}
+
 // Epilogue for the cases the kernel's inline fast path does not cover; kept out
 // of line so that its address arithmetic does not weigh on the main kernel.
 __device__ __noinline__ void store4_general(const DsqConvArgs &a, int m, int o0, v4i acc, float delta_a)
@@ -354,9 +364,9 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
             // left to itself the scheduler sinks each weight load to right before its
             // use, WD taps later, which exposes the full load latency at every tap.  Not
             // where the patch prefetch or the 4-bit 256x128 tile holds many registers (the
-            // variants then spill), and
+            // variants then spill), not on the 4-bit 128x128 tile (measured 3 % slower), and
             // not with two wave groups, where it measured slower)
-            if constexpr (UPT <= 4 && KS == 1 && !(CONT >= 3 && PF == 4)) __builtin_amdgcn_sched_barrier(0);
+            if constexpr (UPT <= 4 && KS == 1 && !(CONT >= 3 && (PF == 4 || (PF == 2 && WP == 2)))) __builtin_amdgcn_sched_barrier(0);
             // consecutive MFMAs go to different accumulators
 #pragma unroll
             for (int kh = 0; kh < KH; ++kh)
@@ -661,9 +671,11 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
     } else {
         // general path: l_a != 0 (terms that depend on which taps are inside the
         // image), NCHW output, raw accumulators wanted, or C_out not a multiple of 4.
-        // (a private copy of the arguments, so that the kernel's own stay in
-        // scalar registers)
-        const DsqConvArgs a_copy = a;
+        // (the out-of-line function takes the arguments by reference: point it at the
+        // kernel-argument segment, where `a` is the first argument, instead of copying the
+        // structure to scratch memory -- the compiler hoists such a copy to the top of the
+        // kernel, where it splits the one batch of argument loads into several round trips)
+        const DsqConvArgs &a_copy = kernarg_conv_args();
 #pragma unroll
         for (int f = 0; f < PF; ++f) {
             const int m = frag_m[f];
