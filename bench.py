@@ -256,6 +256,26 @@ def main():
         result["chained_step"] = {"ms_per_step": round(ch_s * 1e3, 5), "TOPS": round(2.0 * macs / ch_s / 1e12, 2),
                                   "step": "dsq_conv2d_requant per layer (codes in, codes out)"}
         del g_ch
+        # the same with the pixel sums of all layers in one buffer that the step clears with a
+        # single fill at its start (DSQ_CONV_NEXT_SUMS_ZERO) instead of one small launch per layer
+        sizes = [(st.L.N * st.L.Ho * st.L.Wo + 3) // 4 * 4 for st in states for _ in range(st.L.count)]
+        arena = torch.empty(sum(sizes), dtype=torch.int32, device="cuda")
+        zeroed_calls, off = [arena.zero_], 0
+        for st in states:
+            for b in st.bufs[:st.L.count]:
+                n = st.L.N * st.L.Ho * st.L.Wo
+                zeroed_calls.append(lambda st=st, b=b, v=arena[off:off + n]: st.conv_chained_zeroed(b, v))
+                off += (n + 3) // 4 * 4
+        with torch.cuda.stream(stream):
+            for fn in zeroed_calls:
+                fn()
+            torch.cuda.synchronize()
+        g_ch = capture(zeroed_calls)
+        ch_s = timed_replays(g_ch, args.warmup, args.steps) / args.steps
+        result["chained_step_one_clear"] = {"ms_per_step": round(ch_s * 1e3, 5), "TOPS": round(2.0 * macs / ch_s / 1e12, 2),
+                                            "step": "one fill of all layers' pixel sums, then dsq_conv2d_requant per layer "
+                                                    "with DSQ_CONV_NEXT_SUMS_ZERO"}
+        del g_ch, zeroed_calls, arena
     del g_step, step_calls, chained_calls, states
     torch.cuda.empty_cache()
 

@@ -139,12 +139,20 @@ typedef enum { DSQ_PACK_CONTAINER = 0, DSQ_PACK_DENSE3 = 1 } dsq_packing;
  *   on the implicit-GEMM kernels, and DSQ_CONV_KERNEL(7) gives DSQ_ERR_UNSUPPORTED.
  * DSQ_CONV_NEXT_DENSE3 (dsq_conv2d_requant only): codes_next is written in the
  *   dense 3-bit format (bits_next must be 3).
+ * DSQ_CONV_NEXT_SUMS_ZERO (dsq_conv2d_requant only): the caller has set
+ *   pix_code_sum_next to zero (by work enqueued earlier on the same stream), so the
+ *   call launches no clearing kernel of its own.  A network runner that keeps the
+ *   pixel sums of all its layers in one buffer clears them with a single fill per
+ *   forward pass instead of one small launch per layer.  If the buffer is not zero
+ *   the sums of layers wider than a workgroup's tile come out too large by what it
+ *   held.
  * Any other bit set gives DSQ_ERR_UNSUPPORTED.
  */
 #define DSQ_CONV_KERNEL(k) ((k) & 15)
 #define DSQ_CONV_MANY_IN_FLIGHT 0x10
 #define DSQ_CONV_ACT_DENSE3 0x20
 #define DSQ_CONV_NEXT_DENSE3 0x40
+#define DSQ_CONV_NEXT_SUMS_ZERO 0x80
 
 typedef struct {
     int N, C_in, H, W;   /* input activation */
@@ -280,7 +288,8 @@ dsq_status dsq_conv2d(const dsq_conv_desc *d, const void *act_packed,
  *                   with DSQ_CONV_NEXT_DENSE3); codes_bytes is the caller's buffer size
  * pix_code_sum_next device, out, int32[N*Ho*Wo]; the call clears it with a fill
  *                   kernel on the same stream (no memset node, so the call can
- *                   be captured into a HIP graph) and accumulates with integer
+ *                   be captured into a HIP graph; DSQ_CONV_NEXT_SUMS_ZERO says the
+ *                   caller already did) and accumulates with integer
  *                   atomics, which are exact in any order (layers narrow enough
  *                   that a pixel's sum is complete within one workgroup have
  *                   it stored directly)

@@ -20,6 +20,7 @@ DSQ_OK = 0
 DSQ_CONV_MANY_IN_FLIGHT = 0x10
 DSQ_CONV_ACT_DENSE3 = 0x20
 DSQ_CONV_NEXT_DENSE3 = 0x40
+DSQ_CONV_NEXT_SUMS_ZERO = 0x80
 DSQ_PACK_CONTAINER, DSQ_PACK_DENSE3 = 0, 1
 
 

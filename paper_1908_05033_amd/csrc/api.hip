@@ -160,7 +160,7 @@ dsq_status conv_args(const dsq_conv_desc *d, const void *act_packed, const int32
     if (9LL * d->R * d->S * Cp > (1LL << 22)) return DSQ_ERR_UNSUPPORTED;
     if ((long long)d->N * Ho * Wo * dsq_round_up(d->C_out, 64) > kMaxElems) return DSQ_ERR_UNSUPPORTED;
     if ((long long)d->N * Ho * Wo + 1024 > kMaxElems) return DSQ_ERR_UNSUPPORTED;
-    if ((d->flags & ~(15 | DSQ_CONV_MANY_IN_FLIGHT | DSQ_CONV_ACT_DENSE3 | DSQ_CONV_NEXT_DENSE3)) != 0 ||
+    if ((d->flags & ~(15 | DSQ_CONV_MANY_IN_FLIGHT | DSQ_CONV_ACT_DENSE3 | DSQ_CONV_NEXT_DENSE3 | DSQ_CONV_NEXT_SUMS_ZERO)) != 0 ||
         (d->flags & 15) > 7)
         return DSQ_ERR_UNSUPPORTED;
     if ((d->flags & DSQ_CONV_ACT_DENSE3) && d->bits != 3) return DSQ_ERR_UNSUPPORTED;
@@ -183,9 +183,11 @@ dsq_status conv_args(const dsq_conv_desc *d, const void *act_packed, const int32
     a.sw_tap = a.sw_total + Cop;
     a.out = nullptr; a.acc = nullptr; a.out_nchw = 0;
     a.rq = 0; a.rq_scale = nullptr; a.rq_shift = nullptr; a.rq_relu = 0;
-    a.rq_l = 0.f; a.rq_u = 1.f; a.rq_bits = 4; a.rq_dense = 0; a.rq_Cp = 0; a.rq_codes = nullptr; a.rq_pix = nullptr; a.rq_store = 0; a.rq_share = 0;
+    a.rq_l = 0.f; a.rq_u = 1.f; a.rq_bits = 4; a.rq_dense = 0; a.rq_Cp = 0; a.rq_codes = nullptr; a.rq_pix = nullptr; a.rq_store = 0; a.rq_share = 0; a.rq_zeroed = 0;
     for (int j = 0; j < 16; ++j) a.rq_thr[j] = 0.f;
     a.rq_inv_delta = 0.f; a.rq_bias = 0.f;
+    a.rq_fast = 0; a.rq_t_lo = 0.5f; a.rq_t_hi = 0.5f; a.rq_t_margin = -1.f; a.rq_sa_max = 0.f; a.rq_w_max = 0.f;
+    a.rq_inv_dn = 0.0; a.rq_c0 = 0.0;
     return DSQ_OK;
 }
 
@@ -301,7 +303,7 @@ dsq_status dsq_conv2d(const dsq_conv_desc *d, const void *act_packed, const int3
     DsqConvArgs a;
     const dsq_status st = conv_args(d, act_packed, pix_code_sum, l_a, u_a, w_packed, w_aux, a);
     if (st != DSQ_OK) return st;
-    if (d->flags & DSQ_CONV_NEXT_DENSE3) return DSQ_ERR_UNSUPPORTED;     // (only dsq_conv2d_requant writes codes)
+    if (d->flags & (DSQ_CONV_NEXT_DENSE3 | DSQ_CONV_NEXT_SUMS_ZERO)) return DSQ_ERR_UNSUPPORTED;   // (only dsq_conv2d_requant writes codes)
     if (out_layout != DSQ_NHWC && out_layout != DSQ_NCHW) return DSQ_ERR_UNSUPPORTED;
     if (!aligned16(out) || (acc_or_null && !aligned16(acc_or_null))) return DSQ_ERR_ALIGN;
     a.out = out; a.acc = acc_or_null; a.out_nchw = out_layout == DSQ_NCHW;
@@ -349,6 +351,7 @@ dsq_status dsq_conv2d_requant(const dsq_conv_desc *d, const void *act_packed,
                                               dense_next ? DSQ_PACK_DENSE3 : DSQ_PACK_CONTAINER))
         return DSQ_ERR_SIZE;
     a.rq_dense = dense_next;
+    a.rq_zeroed = (d->flags & DSQ_CONV_NEXT_SUMS_ZERO) != 0;
     a.rq = 1; a.rq_scale = scale; a.rq_shift = shift; a.rq_relu = relu != 0;
     a.rq_l = l_next; a.rq_u = u_next; a.rq_bits = bits_next;
     a.rq_Cp = dsq_round_up(a.C_out, 64);
@@ -358,6 +361,22 @@ dsq_status dsq_conv2d_requant(const dsq_conv_desc *d, const void *act_packed,
         const float delta_n = (u_next - l_next) / (float)((1 << bits_next) - 1);
         a.rq_inv_delta = 1.0f / delta_n;
         a.rq_bias = 0.5f;
+        // constants of the code-unit form (see DsqConvArgs)
+        const int top_n = (1 << bits_next) - 1;
+        const double inv_dn = 1.0 / (double)delta_n, c0 = 0.5 - (double)l_next * inv_dn;
+        double e_thr = 0.0;
+        for (int j = 1; j <= top_n; ++j) e_thr = fmax(e_thr, fabs((double)a.rq_thr[j] * inv_dn + c0 - (double)j));
+        const int code0 = host_code(0.0f, l_next, u_next, delta_n, top_n);
+        const double c_max = a.cont == 2 ? 3.0 : 15.0;                   // largest code a container field holds
+        const double depth = (double)a.R * a.R * a.C_in;
+        a.rq_inv_dn = inv_dn; a.rq_c0 = c0;
+        a.rq_t_lo = relu ? (float)code0 + 0.5f : 0.5f;
+        a.rq_t_hi = (float)top_n + 0.5f;
+        a.rq_t_margin = (float)(0.5 - e_thr - 0x1p-20);
+        a.rq_sa_max = (float)(c_max * depth);
+        a.rq_w_max = (float)c_max;
+        a.rq_fast = c_max * c_max * depth < 0x1p24 && delta_n >= 0x1p-60f && delta_n <= 0x1p60f &&
+                    fabsf(l_next) <= 0x1p60f && a.rq_t_margin > 0.0f;
     }
     return launch_conv(a, (hipStream_t)hip_stream);
 }

@@ -162,15 +162,18 @@ __device__ __forceinline__ uint32_t dsq_requant4_thr(const float (&y)[4], const 
 // q = 0..3; bytes[q] carries their codes one per byte.  Lanes L and L^32 hold
 // the two halves of every 8-channel word and swap them; the h = 0 lane then
 // stores the 16 (4-bit containers), 12 (dense 3-bit) or 8 (2-bit) bytes of the pixel.  Must be
-// called by all 64 lanes; `m` < 0 marks a lane without a pixel.  Returns the
-// pixel's code sum over these 32 channels (both lanes of the pair get it).
+// called by all 64 lanes; `m` < 0 marks a lane without a pixel.  Returns, in
+// the h = 0 lane, the pixel's code sum over these 32 channels.
 __device__ __forceinline__ int dsq_requant_store32(const DsqConvArgs &a, int m, int o_tile, int h,
                                                    const uint32_t (&bytes)[4], int sum)
 {
+    // (v_permlane32_swap exchanges the upper half of its first operand with the lower
+    // half of its second: element 1 of the result holds, in lanes 0..31, the values
+    // of lanes 32..63)
     uint32_t other[4];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) other[q] = (uint32_t)__shfl_xor((int)bytes[q], 32);
-    const int total = sum + __shfl_xor(sum, 32);
+    for (int q = 0; q < 4; ++q) other[q] = __builtin_amdgcn_permlane32_swap(bytes[q], bytes[q], false, false)[1];
+    const int total = sum + (int)__builtin_amdgcn_permlane32_swap((uint32_t)sum, (uint32_t)sum, false, false)[1];
     if (h == 0 && m >= 0 && o_tile < a.rq_Cp) {
         char *dst = (char *)a.rq_codes;
         if (a.rq_dense) {

@@ -190,8 +190,8 @@ hipError_t launch_fc(const DsqConvArgs &a, hipStream_t stream)
     // (chained mode also writes the code-0 padding channels up to a multiple of 64)
     dim3 grid((M + 31) / 32, ((a.rq ? a.rq_Cp : a.C_out) + 31) / 32);
     // chained mode: the channel tiles add to the next layer's pixel sums, which a
-    // fill kernel clears first (no memset node: the call may be under graph capture)
-    if (a.rq) {
+    // fill kernel clears first unless the caller did (no memset node: the call may be under graph capture)
+    if (a.rq && !a.rq_zeroed) {
         const hipError_t e = dsq_launch_fill_zero(a.rq_pix, (size_t)M, stream);
         if (e != hipSuccess) return e;
     }

@@ -56,14 +56,14 @@ bool plan_patch(const DsqConvArgs &a, int BP, int BC, int PF, int CT, int UPT, i
         // buffer of a group: leave it out, so that more workgroups fit a CU
         const int nbuf = a.Cp / 64 > KS ? 2 : 1;
         p.aux_off = nbuf * KS * p.buf_bytes > epi_bytes ? nbuf * KS * p.buf_bytes : epi_bytes;
-        if (plan_lds_bytes(p, BC) > lds_limit) continue;
+        if (plan_lds_bytes(p, BC, a.rq != 0) > lds_limit) continue;
         if (p.units > 256 * UPT) continue;
         const long long tiles = (long long)p.tiles_w * p.row_tiles;
         // keep the operands of the index arithmetic small
         if (tiles * ((a.C_out + BC - 1) / BC) >= (1 << 22) || (long long)a.N * Hp >= (1 << 22) || NHo >= (1 << 22)) continue;
         // equal work: prefer a footprint that lets three (else two) workgroups share a CU,
         // then the smaller patch
-        const int lds_bytes = plan_lds_bytes(p, BC);
+        const int lds_bytes = plan_lds_bytes(p, BC, a.rq != 0);
         const long long cost = tiles * 100000 + (lds_bytes <= 52 * 1024 ? 0 : lds_bytes <= 78 * 1024 ? 20000 : 40000) +
                                (long long)p.PR * p.PC;
         if (!found || cost < best_cost) { best = p; best_cost = cost; found = true; }
@@ -167,7 +167,7 @@ int dsq_conv_patch_describe(const DsqConvArgs &a, int force_tile, char *text, si
     snprintf(text, n, "patch kernel: container %d, %dx%d filter, tile %dx%d (pixels x channels), %d wave group%s, "
              "%d fetch units per thread%s; strip width %d, patch %dx%d, %d workgroups, %d LDS bytes",
              a.cont, a.R, a.R, 32 * tc.PF * tc.WP, BC, ks, ks == 1 ? "" : "s", upt,
-             a.rq ? ", chained epilogue" : "", pl.TW, pl.PR, pl.PC, blocks, plan_lds_bytes(pl, BC));
+             a.rq ? ", chained epilogue" : "", pl.TW, pl.PR, pl.PC, blocks, plan_lds_bytes(pl, BC, a.rq != 0));
     return 1;
 }
 

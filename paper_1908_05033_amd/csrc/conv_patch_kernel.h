@@ -98,6 +98,55 @@ __device__ __noinline__ void store4_general(const DsqConvArgs &a, int m, int o0,
     dsq_store4(a, px, m, o0, acc, delta_a);
 }
 
+// Chained mode, per output channel o: the constants of the code-unit form of the
+// layer-to-layer map.  With P = Da*Dw[o], Q = Da*l_w[o] (binary64, exact), scale sc
+// and shift sh, the real value of the next layer's input in units of its quantizer
+// step is
+//   t = ((P*ACC + Q*SA)*sc + sh - l_n)/D_n + 1/2 = A*(ACC + rho*SA) + s,
+//   A = P*sc/D_n, rho = Q/P = l_w/Dw, s = sh/D_n + c0, c0 = 1/2 - l_n/D_n,
+// and the code is floor(t) clamped to the code range.  The kernel evaluates
+//   u = fma(SA, rho32, ACC)             one rounding, of the small difference: the two
+//                                       large terms cancel inside the fma
+//   t = fma(u, A32, fma(SA, B32, s32))  B = A*(rho - rho32): the part of rho that
+//                                       binary32 drops
+// The exact sequence (fp32 value of the layer, times scale, plus shift: three
+// roundings) and this one (three roundings, four rounded constants) each differ from
+// the real t by a few 2^-24 of |t| + S, S = |sh|/D_n + |c0|, in total less than
+//   E = 2^-21*(2^bits + S) + 2^-45*|Q*sc/D_n|*SA_max
+// for t inside the code range (6|t| + 7S times 2^-24 to first order; the last term
+// covers the rounding of B and of the fma that uses it).  Outside the range both
+// clamp alike when E < 1/2.  Returns te = margin - E (margin: see DsqConvArgs), what
+// |fract(t) - 1/2| must stay below for floor(t) to be the exact sequence's code;
+// te = -1 (never safe) for channels whose magnitudes would let an intermediate of
+// either sequence overflow, or lose bits to denormals, and when the host disabled
+// the form: those keep harmless constants, so that t stays finite.  Channels past
+// C_out get constants that give code 0 safely (their bytes are blanked anyway).
+//
+// `unit`: the kernel's accumulators hold ACC/unit (the FP4 form counts in quarter
+// units): A*unit and rho32/unit are stored, both exact scalings by a power of two.
+__device__ __forceinline__ float chained_channel_constants(const DsqConvArgs &a, int o, double P, double Q, float scale,
+                                                           float shift, float unit, float4 &k)
+{
+    k = make_float4(0.f, 0.f, 0.f, 0.5f);
+    if (o >= a.C_out) return 0.25f;
+    const double sc = (double)scale, sh = (double)shift, inv_dn = a.rq_inv_dn;
+    const double rho = Q / P;
+    const float rho32 = (float)rho;
+    const double A = P * sc * inv_dn;
+    const double s = __builtin_fma(sh, inv_dn, a.rq_c0);
+    const double S = __builtin_fabs(sh) * inv_dn + __builtin_fabs(a.rq_c0);
+    const double samax = (double)a.rq_sa_max;
+    const double E = 0x1p-21 * ((double)(1 << a.rq_bits) + S) + 0x1p-45 * __builtin_fabs(Q * sc * inv_dn) * samax;
+    const double ymax = (__builtin_fabs(P) * (double)a.rq_w_max + __builtin_fabs(Q)) * samax;    // bound on the layer's |output|
+    // (every comparison is false for a NaN, which then ends in te = -1)
+    const bool ok = a.rq_fast && ymax < 0x1p100 && ymax * __builtin_fabs(sc) < 0x1p100 && __builtin_fabs(sh) < 0x1p100 &&
+                    (__builtin_fabs(sc) + 1.0) * inv_dn < 0x1p100 && __builtin_fabs(A) < 0x1p60 &&
+                    __builtin_fabs(rho) < 0x1p20 && E < (double)a.rq_t_margin;
+    if (!ok) return -1.0f;
+    k = make_float4((float)A * unit, rho32 / unit, (float)(A * (rho - (double)rho32)), (float)s);
+    return (float)((double)a.rq_t_margin - E);
+}
+
 // RQ selects the chained-mode epilogue at compile time, so that the plain
 // kernels' register allocation is exactly what it is without that mode.
 template <int CONT, int R, int WP, int WC, int PF, int CT, int UPT, int WD, int OCC, int KS, bool RQ>
@@ -129,6 +178,10 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
     float *ss_lds = reinterpret_cast<float *>(lds + ((pl.aux_off + 2 * BC * 8 + pl.PR * pl.PC * 4 + 15) & ~15));
     // chained mode: the next quantizer's thresholds as 16 (lower, upper) pairs
     float2 *thr_lds = reinterpret_cast<float2 *>(ss_lds + 2 * BC);
+    // chained mode: per channel the constants (A, rho, B, s) of the code-unit form, and the
+    // largest distance from 1/2 of the fraction of t at which every channel's code is safe
+    float4 *ft_lds = reinterpret_cast<float4 *>(thr_lds + 16);
+    int *te_lds = reinterpret_cast<int *>(ft_lds + BC);              // (the bits of a float: see below)
 
     // KS = 2: two groups of four waves work on alternating 64-channel blocks of K
     // (each with its own patch buffers) and add their accumulators at the end, so
@@ -419,6 +472,7 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
                 hi = tid + 1 == j ? a.rq_thr[j] : hi;
             }
             thr_lds[tid] = make_float2(lo, hi);
+            if (tid == 0) *te_lds = __float_as_int(0.5f);
         }
     }
     lds_barrier();
@@ -440,6 +494,7 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
     const bool fast = !a.out_nchw && (a.C_out & 3) == 0 && a.l_a == 0.0f && a.acc == nullptr;
     // per fragment: SA = code sums of the patch pixels under the taps (0 in the padding)
     double dsa[PF];
+    float fsa[PF];          // (the same sums in binary32: exact, they stay below 2^24 wherever this is used)
     auto sum_sa = [&]() {
 #pragma unroll
         for (int f = 0; f < PF; ++f) {
@@ -447,6 +502,7 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
 #pragma unroll
             for (int t = 0; t < T; ++t) sa += pix_lds[frag_pp[f] + (t / R) * pl.PC + (t % R)];
             dsa[f] = (double)sa;
+            fsa[f] = (float)sa;
         }
     };
     // Da*Dw and Da*l_w of this lane's channels of one tile: 4 groups of 4
@@ -475,13 +531,15 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
 
     // the exact integer sums (the FP4 form accumulates them in quarter units)
     v16i acc[PF][CT];
+    if constexpr (!(RQ && F4 && KS == 1)) {
 #pragma unroll
-    for (int f = 0; f < PF; ++f)
+        for (int f = 0; f < PF; ++f)
 #pragma unroll
-        for (int c = 0; c < CT; ++c) {
-            if constexpr (F4) acc[f][c] = dsq_fp4_acc_to_int(macc[f][c]);
-            else acc[f][c] = macc[f][c];
-        }
+            for (int c = 0; c < CT; ++c) {
+                if constexpr (F4) acc[f][c] = dsq_fp4_acc_to_int(macc[f][c]);
+                else acc[f][c] = macc[f][c];
+            }
+    }
 
     // ---- epilogue --------------------------------------------------------------
     if (!early_tables) sum_sa();
@@ -492,6 +550,21 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
     // channels (128 bytes) of 8 pixels instead of 16 bytes of 32 pixels.
     constexpr int ROWB = 128 + 16;                // staged bytes per pixel (+16: bank spread)
     constexpr int EPI_WAVE = 32 * ROWB + PF * 128;
+    // chained mode, one wave group: the code-unit form reads the FP4 accumulators as
+    // they are (quarter units); the integers are only formed where the exact sequence runs
+    constexpr bool RAWF = RQ && F4 && KS == 1;
+    if (RQ && grp == 0 && tid < BC) {
+        const float te = chained_channel_constants(a, blk_y * BC + tid, pq_lds[tid], pq_lds[BC + tid], ss_lds[tid],
+                                                   ss_lds[BC + tid], RAWF ? 4.0f : 1.0f, ft_lds[tid]);
+        // the smallest margin of the workgroup's channels: reduced over the wave first
+        // (BC is a multiple of 64, so whole waves get here), then one LDS operation per
+        // wave (te is -1 or in (0, 1/2]: as signed integers the bit patterns of such
+        // floats are ordered like the floats)
+        float m = te;
+#pragma unroll
+        for (int sft = 32; sft >= 1; sft >>= 1) m = __builtin_fminf(m, __shfl_xor(m, sft));
+        if (lane == 0) atomicMin(te_lds, __float_as_int(m));
+    }
     lds_barrier();                              // every wave is done with the patch buffers
     if (KS == 2) {
         // each group finishes the channel tiles c with c % 2 == grp: it hands the
@@ -542,45 +615,77 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
         const int top_n = (1 << a.rq_bits) - 1;
         const float relu_floor = a.rq_relu ? 0.0f : -__builtin_inff();
         const float l_n = a.rq_l, u_n = a.rq_u, inv_delta_n = a.rq_inv_delta;
-        const float t1 = a.rq_thr[1], t2 = a.rq_thr[2], t3 = a.rq_thr[3];
-        auto chained = [&](auto linear) {
-            constexpr bool LINEAR = decltype(linear)::value;
+        const float t_lo = a.rq_t_lo, t_hi = a.rq_t_hi;
+        const float te_wg = __int_as_float(*te_lds);
 #pragma unroll
-            for (int c = 0; c < CT; ++c) {
-                if (KS == 2 && (c & 1) != grp) continue;
-                const int o_tile = (ct0 + c) * 32;
-                const int ol = (wc * CT + c) * 32 + 4 * h;   // this lane's first channel inside the workgroup
-                // bytes of channels >= C_out are blanked (their codes must be 0)
-                uint32_t mask[4];
+        for (int c = 0; c < CT; ++c) {
+            if (KS == 2 && (c & 1) != grp) continue;
+            const int o_tile = (ct0 + c) * 32;
+            const int ol = (wc * CT + c) * 32 + 4 * h;   // this lane's first channel inside the workgroup
+            // bytes of channels >= C_out are blanked (their codes must be 0)
+            uint32_t mask[4];
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int left = a.C_out - (o_tile + 8 * q + 4 * h);      // valid channels from here on
-                    mask[q] = left >= 4 ? 0xFFFFFFFFu : left <= 0 ? 0u : (1u << (8 * left)) - 1u;
-                }
+            for (int q = 0; q < 4; ++q) {
+                const int left = a.C_out - (o_tile + 8 * q + 4 * h);      // valid channels from here on
+                mask[q] = left >= 4 ? 0xFFFFFFFFu : left <= 0 ? 0u : (1u << (8 * left)) - 1u;
+            }
+            // The code in code units, t = A*(ACC + rho*SA) + (B*SA + s) (see
+            // chained_channel_constants): seven or eight binary32 instructions per output,
+            // no binary64; the constants of four channels serve all fragments.  far[f]: the
+            // largest distance of a fract(t) from 1/2 among the outputs of fragment f.
+            uint32_t bytes[PF][4];
+            float far[PF];
+#pragma unroll
+            for (int f = 0; f < PF; ++f) far[f] = 0.0f;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                float4 k[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) k[j] = ft_lds[ol + 8 * q + j];
 #pragma unroll
                 for (int f = 0; f < PF; ++f) {
-                    uint32_t bytes[4];
+                    int cd[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        float fa;
+                        if constexpr (RAWF) fa = macc[f][c][4 * q + j];
+                        else fa = (float)acc[f][c][4 * q + j];
+                        const float u = __builtin_fmaf(fsa[f], k[j].y, fa);
+                        const float t = __builtin_fmaf(u, k[j].x, __builtin_fmaf(fsa[f], k[j].z, k[j].w));
+                        const float tc = __builtin_amdgcn_fmed3f(t, t_lo, t_hi);
+                        cd[j] = (int)tc;
+                        far[f] = __builtin_fmaxf(far[f], __builtin_fabsf(__builtin_amdgcn_fractf(tc) - 0.5f));
+                    }
+                    bytes[f][q] = dsq_bytes4(cd[0], cd[1], cd[2], cd[3]) & mask[q];
+                }
+            }
+#pragma unroll
+            for (int f = 0; f < PF; ++f) {
+                if (__builtin_expect(__builtin_amdgcn_ballot_w64(!(far[f] < te_wg)) != 0, 0)) {
+                    // the exact sequence: the binary32 value the plain call stores, scale,
+                    // shift, ReLU and the quantizer as a step function
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
                         float y[4];
 #pragma unroll
-                        for (int j = 0; j < 4; ++j)
-                            y[j] = (float)__builtin_fma(pq_lds[ol + 8 * q + j], (double)acc[f][c][4 * q + j],
-                                                        pq_lds[BC + ol + 8 * q + j] * dsa[f]);
+                        for (int j = 0; j < 4; ++j) {
+                            int ai;
+                            if constexpr (RAWF) ai = (int)(macc[f][c][4 * q + j] * 4.0f);
+                            else ai = acc[f][c][4 * q + j];
+                            y[j] = (float)__builtin_fma(pq_lds[ol + 8 * q + j], (double)ai, pq_lds[BC + ol + 8 * q + j] * dsa[f]);
+                        }
                         const float4 s4 = *reinterpret_cast<const float4 *>(ss_lds + ol + 8 * q);
                         const float4 b4 = *reinterpret_cast<const float4 *>(ss_lds + BC + ol + 8 * q);
                         const float sc[4] = {s4.x, s4.y, s4.z, s4.w}, sh[4] = {b4.x, b4.y, b4.z, b4.w};
-                        bytes[q] = dsq_requant4_thr<LINEAR>(y, sc, sh, relu_floor, l_n, u_n, inv_delta_n, top_n,
-                                                            t1, t2, t3, thr_lds, mask[q]);
+                        bytes[f][q] = dsq_requant4_thr<false>(y, sc, sh, relu_floor, l_n, u_n, inv_delta_n, top_n,
+                                                              0.f, 0.f, 0.f, thr_lds, mask[q]);
                     }
-                    const int sum = dsq_bytesum(bytes[0]) + dsq_bytesum(bytes[1]) + dsq_bytesum(bytes[2]) +
-                                    dsq_bytesum(bytes[3]);
-                    psum[f] += dsq_requant_store32(a, frag_m[f], o_tile, h, bytes, sum);
                 }
+                const int sum = (int)__builtin_amdgcn_sad_u8(bytes[f][3], 0u, __builtin_amdgcn_sad_u8(bytes[f][2], 0u,
+                                __builtin_amdgcn_sad_u8(bytes[f][1], 0u, __builtin_amdgcn_sad_u8(bytes[f][0], 0u, 0u))));
+                psum[f] += dsq_requant_store32(a, frag_m[f], o_tile, h, bytes[f], sum);
             }
-        };
-        if (top_n <= 3) chained(std::true_type{});
-        else chained(std::false_type{});
+        }
         // The waves that share a row of pixel fragments (wave columns, wave groups)
         // hand their sums to the row's first wave through their staging slices
         // (integer adds: exact in any order) ...
@@ -703,11 +808,12 @@ inline uint32_t division_constant(int d)
     return m > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)m;
 }
 
-inline int plan_lds_bytes(const PatchPlan &p, int BC)
+inline int plan_lds_bytes(const PatchPlan &p, int BC, bool chained)
 {
     // tables behind the buffers: Da*Dw, Da*l_w (binary64), the patch pixels' code
-    // sums, and the chained mode's scale, shift and quantizer thresholds
-    return ((p.aux_off + 2 * BC * 8 + p.PR * p.PC * 4 + 15) & ~15) + 2 * BC * 4 + 16 * 8;
+    // sums, the chained mode's scale, shift and quantizer thresholds and (chained
+    // kernels only) its per-channel constants of the code-unit form
+    return ((p.aux_off + 2 * BC * 8 + p.PR * p.PC * 4 + 15) & ~15) + 2 * BC * 4 + 16 * 8 + (chained ? BC * 16 + 16 : 0);
 }
 
 template <int CONT, int R, int WP, int WC, int PF, int CT, int UPT, int WD, int OCC, int KS, bool RQ>
@@ -715,14 +821,14 @@ hipError_t launch_kernel(const DsqConvArgs &a, const PatchPlan &pl, hipStream_t 
 {
     auto kern = conv_patch_kernel<CONT, R, WP, WC, PF, CT, UPT, WD, OCC, KS, RQ>;
     const int BC = 32 * CT * WC;
-    const size_t lds = (size_t)plan_lds_bytes(pl, BC);      // pl.aux_off already accounts for KS
+    const size_t lds = (size_t)plan_lds_bytes(pl, BC, RQ);      // pl.aux_off already accounts for KS
     if (lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
     // chained mode, layer wider than the tile: the workgroups add to the next
-    // layer's pixel sums, which a fill kernel clears first
-    if (RQ && !a.rq_store) {
+    // layer's pixel sums, which a fill kernel clears first (unless the caller did)
+    if (RQ && !a.rq_store && !a.rq_zeroed) {
         const hipError_t e = dsq_launch_fill_zero(a.rq_pix, (size_t)a.N * a.Ho * a.Wo, stream);
         if (e != hipSuccess) return e;
     }

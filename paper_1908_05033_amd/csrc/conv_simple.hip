@@ -115,8 +115,8 @@ hipError_t dsq_launch_conv_simple(const DsqConvArgs &a, hipStream_t stream)
     const int M = a.N * a.Ho * a.Wo;
     dim3 grid((M + 31) / 32, ((a.rq ? a.rq_Cp : a.C_out) + 127) / 128);
     // chained mode: the workgroups add to the next layer's pixel sums, which a
-    // fill kernel clears first (no memset node: the call may be under graph capture)
-    if (a.rq) {
+    // fill kernel clears first unless the caller did (no memset node: the call may be under graph capture)
+    if (a.rq && !a.rq_zeroed) {
         const hipError_t e = dsq_launch_fill_zero(a.rq_pix, (size_t)M, stream);
         if (e != hipSuccess) return e;
     }

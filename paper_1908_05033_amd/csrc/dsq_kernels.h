@@ -45,9 +45,25 @@ struct DsqConvArgs {
     // is off by at most one.
     float rq_thr[16];
     float rq_inv_delta, rq_bias;
+    // The LDS-patch kernel first decides a code in "code units":
+    //   t = ((y*scale + shift) - l)/Delta + 1/2,  code = floor(clamp(t, rq_t_lo, rq_t_hi)),
+    // evaluated in binary32 from per-channel constants (conv_patch_kernel.h), and keeps
+    // that code when t is farther from every integer than the error bound of the
+    // evaluation; otherwise it falls back on the exact sequence above.  The host part
+    // of that bound: rq_t_margin = 1/2 - max_j |t(rq_thr[j]) - j| - 2^-20 (how far the
+    // true thresholds sit from the integers of the ideal staircase, plus slack for
+    // absolute rounding errors); rq_t_lo = 1/2, or code(0) + 1/2 under the ReLU;
+    // rq_t_hi = 2^bits - 1/2; rq_inv_dn = 1/Delta and rq_c0 = 1/2 - l/Delta in binary64;
+    // rq_sa_max bounds the sum of activation codes under one output, rq_w_max the
+    // weight codes.  rq_fast = 0 (deep layers whose accumulators pass 2^24, extreme
+    // ranges) sends every output through the exact sequence.
+    int rq_fast;
+    float rq_t_lo, rq_t_hi, rq_t_margin, rq_sa_max, rq_w_max;
+    double rq_inv_dn, rq_c0;
     int rq_Cp;                // C_out rounded up to 64
     void *rq_codes;           // packed codes of the next layer's input
     int32_t *rq_pix;          // [N*Ho*Wo]; the kernels add to it (cleared before the launch) unless rq_store
+    int rq_zeroed;            // the caller cleared rq_pix (DSQ_CONV_NEXT_SUMS_ZERO): launch no fill kernel
     int rq_share;             // set by a launcher: the waves of a workgroup add up their pixel sums in LDS first
     int rq_store;             // set by a launcher whose workgroups each hold all channels of their
                               // pixels: plain stores to rq_pix, nothing to clear

@@ -96,6 +96,9 @@ class LayerState:
             # (the chained call's descriptor: the same, plus the format of the codes it writes)
             b.desc_chained = B.make_desc(L.N, L.C_in, L.H, L.W, L.C_out, L.R, L.S, L.stride, L.pad, L.bits,
                                          flags | (B.DSQ_CONV_NEXT_DENSE3 if dense3 else 0))
+            # (and for a caller that clears the next layer's pixel sums itself)
+            b.desc_chained_z = B.make_desc(L.N, L.C_in, L.H, L.W, L.C_out, L.R, L.S, L.stride, L.pad, L.bits,
+                                           flags | B.DSQ_CONV_NEXT_SUMS_ZERO | (B.DSQ_CONV_NEXT_DENSE3 if dense3 else 0))
             self.bufs.append(b)
         self.wp, self.aux = self.bufs[0].w_packed, self.bufs[0].w_aux
         self.l_a, self.u_a = 0.0, float(u_a)
@@ -133,6 +136,12 @@ class LayerState:
         B.dsq_conv2d_requant(b.desc_chained, b.act_packed, b.pix_code_sum, self.l_a, self.u_a, self.wp, self.aux,
                              self.scale, self.shift, True, self.l_n, self.u_n, self.bits_next,
                              b.codes_next, b.pix_next)
+
+    def conv_chained_zeroed(self, b, pix_next):
+        """The chained call into pixel sums the caller has cleared (DSQ_CONV_NEXT_SUMS_ZERO)."""
+        B.dsq_conv2d_requant(b.desc_chained_z, b.act_packed, b.pix_code_sum, self.l_a, self.u_a, self.wp, self.aux,
+                             self.scale, self.shift, True, self.l_n, self.u_n, self.bits_next,
+                             b.codes_next, pix_next)
 
     def quant_next(self, b):
         """What the chained call saves: quantizing the fp32 output for the next layer."""

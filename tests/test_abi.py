@@ -131,7 +131,11 @@ def test_conv_flags_are_validated_per_call():
     state): unknown bits and kernel numbers above 7 are refused."""
     assert _c(flags=0x20) == 5 and _c(flags=0x100) == 5 and _c(flags=-1) == 5
     assert _c(flags=8) == 5 and _c(flags=15) == 5
-    assert _r(flags=0x40) == 5 and _r(flags=9) == 5
+    assert _r(flags=0x40) == 5 and _r(flags=9) == 5 and _r(flags=0x100) == 5
+    # the chained call's own flags are refused by the plain call and pass the chained call's flag
+    # check (which then fails on the misaligned output)
+    assert _c(flags=B.DSQ_CONV_NEXT_SUMS_ZERO) == 5
+    assert _r(flags=B.DSQ_CONV_NEXT_SUMS_ZERO, codes=FAKE + 4) == 6
     # valid flag values get past the flag check (and fail later, on the misaligned output)
     for flags in (0, 1, 7, B.DSQ_CONV_MANY_IN_FLIGHT, B.DSQ_CONV_MANY_IN_FLIGHT | B.DSQ_CONV_KERNEL(4)):
         assert _c(flags=flags, out=FAKE + 4) == 6

@@ -15,7 +15,8 @@ with the oracle:
   * the chained call's codes for the next layer: equal to the oracle's
     requantization of its own output except where that value lies within 1e-4
     of a quantizer midpoint (there: at most one code apart), and pixel sums
-    equal to the sums of the codes written.
+    equal to the sums of the codes written; and the codes equal those of the
+    simple kernel bit for bit.
 
 The launch plans chosen at these sizes (tile, wave groups, fetch units per
 thread, strip width, ragged last tile, per-XCD tile ranges) are not reached by
@@ -77,4 +78,11 @@ def test_every_element_of_the_layer_at_full_size(cfg, li, bits):
         assert np.array_equal(pix, got_c.sum(axis=3, dtype=np.int64)), "pixel sums are not the sums of the codes"
         if nbad == 0:
             assert np.array_equal(pix, want_sum)
+        if not many:
+            # the simple kernel runs the exact sequence (the recipe with its division) on every
+            # output; the tuned kernels decide most codes from a cheaper evaluation: same bits
+            ref_c, ref_pix, *_ = run_requant_gpu(layer, inp, scale, shift, True, l_n, u_n, bits, kernel=1)
+            assert np.array_equal(got_c, ref_c), "codes differ from the simple kernel's"
+            assert np.array_equal(pix, ref_pix)
+            del ref_c, ref_pix
         del got_c, pix

@@ -160,6 +160,29 @@ def test_without_affine_and_two_calls_in_a_row(kernel):
     assert np.array_equal(pixd.cpu().numpy().reshape(pix.shape), pix)
 
 
+@pytest.mark.parametrize("kernel", [0, 1, 3, 4, 6, 7])
+@pytest.mark.parametrize("geom", [(2, 64, 9, 7, 64, 3, 1, 1), (2, 256, 6, 6, 256, 3, 1, 1), (1, 320, 7, 7, 300, 1, 1, 0),
+                                  (40, 1024, 1, 1, 256, 1, 1, 0)])
+def test_caller_cleared_pixel_sums(geom, kernel):
+    """DSQ_CONV_NEXT_SUMS_ZERO: the caller clears the next layer's pixel sums and the
+    call launches no clearing kernel: same codes and sums as the plain chained call.
+    (With a buffer that is not zero, layers wider than the tile add on top of it:
+    documented; narrow ones store.)"""
+    N, Ci, H, W, Co, R, stride, pad = geom
+    layer, inp = inputs.small_random_case(sum(geom), N, Ci, H, W, Co, R, stride, pad, 4, l_a=0.0, u_a=2.1)
+    scale, shift = inputs.affine_params(sum(geom), Co)
+    want_c, want_pix, codes, pix, buf = run_requant_gpu(layer, inp, scale, shift, True, 0.0, 2.0, 4, kernel)
+    codes2 = torch.full_like(codes, 0xEE)
+    pix2 = torch.zeros_like(pix)
+    buf.desc.flags |= B.DSQ_CONV_NEXT_SUMS_ZERO
+    B.dsq_conv2d_requant(buf.desc, buf.act_packed, buf.pix_code_sum, inp["l_a"], inp["u_a"], buf.w_packed, buf.w_aux,
+                         torch.from_numpy(scale).cuda(), torch.from_numpy(shift).cuda(), True, 0.0, 2.0, 4, codes2, pix2)
+    torch.cuda.synchronize()
+    assert torch.equal(codes2, codes)
+    assert torch.equal(pix2, pix)
+    assert np.array_equal(pix.cpu().numpy().reshape(want_pix.shape), want_c.astype(np.int64).sum(axis=3))
+
+
 def test_chain_of_two_layers_matches_the_oracle_chain():
     """Layer A (3x3, chained output) feeds layer B (1x1, fp32 output) without
     the activation ever being stored as floats; the oracle runs the same two
@@ -231,6 +254,61 @@ def test_argument_errors():
         with pytest.raises(B.DsqError) as e:
             B.dsq_conv2d_requant(*args, *tail)
         assert e.value.status == status
+
+
+ULP_OFFSETS = [0.0, 2.0 ** -24, -2.0 ** -24, 2.0 ** -22, -2.0 ** -22, 1e-6, -1e-6, 3e-6, -3e-6, 1e-5, -1e-5, 1e-4, -1e-4,
+               2.0 ** -19, -2.0 ** -19, 0.25]
+
+
+@pytest.mark.parametrize("kernel", [0, 3, 4, 6])
+@pytest.mark.parametrize("bits,bits_n,relu", [(4, 2, False), (2, 2, True), (3, 4, False), (4, 4, True), (2, 3, False)])
+@pytest.mark.parametrize("geom", [(2, 64, 9, 7, 64, 3, 1, 1), (2, 256, 6, 6, 256, 3, 1, 1), (1, 24, 10, 11, 144, 1, 1, 0),
+                                  (2, 96, 7, 9, 40, 3, 2, 1)])
+def test_values_on_and_beside_the_quantizer_steps(geom, bits, bits_n, relu, kernel):
+    """The tuned kernels decide most codes from a cheap binary32 evaluation of the
+    whole layer-to-layer map and keep the exact sequence (reading P13) for values
+    too close to a step of the next quantizer.  Here the layer is integer valued
+    (Da = Dw = 1, l_w = -1: y = ACC - SA) and scale, shift and the next range are
+    chosen so that the exact value lands on a step of the next quantizer, or a few
+    ulps up to 1e-4 beside it, for a large share of the outputs; the codes must
+    equal those of the simple kernel (the recipe itself, with its division) bit
+    for bit, and the oracle's."""
+    N, Ci, H, W, Co, R, stride, pad = geom
+    top = (1 << bits) - 1
+    layer, inp = inputs.small_random_case(sum(geom) + 7 * bits, N, Ci, H, W, Co, R, stride, pad, bits, l_a=0.0, u_a=float(top))
+    g = torch.Generator().manual_seed(inputs.BASE_SEED + 4242 + sum(geom))
+    inp["x"] = torch.randint(0, top + 1, inp["x"].shape, generator=g).to(torch.float32)
+    # weight levels mostly 0 (code 1), about eight other levels per output: y has a small spread
+    # although ACC and SA are large, so that many outputs share the few values next to a step
+    wv = torch.randint(-1, top, inp["w"].shape, generator=g).to(torch.float32)
+    keep = torch.rand(inp["w"].shape, generator=g) < 8.0 / (Ci * R * R)
+    inp["w"] = torch.where(keep, wv, torch.zeros_like(wv))
+    inp["l_w"] = np.full(Co, -1.0, np.float32)
+    inp["u_w"] = np.full(Co, top - 1.0, np.float32)
+    a_code, w_code = oracle_layer(layer, inp)
+    y = oracle.conv_real(a_code, inp["l_a"], inp["u_a"], w_code, inp["l_w"], inp["u_w"], bits, stride, pad)
+    assert np.array_equal(y, np.round(y))
+    top_n = (1 << bits_n) - 1
+    l_n, u_n = -0.5 * top_n, 0.5 * top_n                         # D_n = 1: steps at the half-integers... shifted below
+    # (powers of two: z stays on a binary grid that contains the steps; sized so that the
+    # outputs of a channel spread over about the next quantizer's range)
+    s0 = 2.0 ** -int(np.ceil(np.log2(max(y.std(axis=(0, 2, 3)).mean() / top_n, 1.0))))
+    scale = (s0 * np.array([1.0, 0.5, -1.0, 0.25]))[np.arange(Co) % 4].astype(np.float32)
+    centre = np.median(y, axis=(0, 2, 3))
+    off = np.array(ULP_OFFSETS, np.float64)[(np.arange(Co) // 4) % len(ULP_OFFSETS)]
+    # z = y*scale + shift; steps of the quantizer sit at l_n + (j - 1/2): put z of the channel's
+    # median output on such a step, plus the offset
+    shift = (np.float64(l_n) + 0.5 - np.round(centre) * scale.astype(np.float64) + off).astype(np.float32)
+    z = oracle.affine_relu(y, scale, shift, relu)
+    want = oracle.quantize(z, l_n, u_n, bits_n)
+    ref, ref_pix, *_ = run_requant_gpu(layer, inp, scale, shift, relu, l_n, u_n, bits_n, 1)
+    assert np.array_equal(ref[..., :Co].transpose(0, 3, 1, 2), want)          # (y is exact here: no midpoint slack)
+    got, pix, *_ = run_requant_gpu(layer, inp, scale, shift, relu, l_n, u_n, bits_n, kernel)
+    assert np.array_equal(got, ref)
+    assert np.array_equal(pix, ref_pix)
+    d = np.abs((z.astype(np.float64) - l_n + 0.5) - np.round(z.astype(np.float64) - l_n + 0.5))
+    inside = (z > l_n - 1) & (z < u_n + 1)
+    assert (inside & (d < 2e-4)).sum() > z.size // 200, "the case must put many outputs next to a step"
 
 
 def _oracle_threshold(l, u, bits, j):
