@@ -139,11 +139,10 @@ __device__ __forceinline__ uint32_t dsq_requant4(const DsqConvArgs &a, int o0, c
 // relu_floor is 0 with ReLU and -inf without (max(z, -inf) = z; a NaN becomes
 // -inf, which has code 0 like the NaN itself); byte_mask blanks the bytes of
 // channels >= C_out.
-template <bool LINEAR>
 __device__ __forceinline__ uint32_t dsq_requant4_thr(const float (&y)[4], const float (&sc)[4],
                                                      const float (&sh)[4], float relu_floor, float l_n,
-                                                     float u_n, float inv_delta, int top_n, float t1, float t2,
-                                                     float t3, const float2 *thr_pairs, uint32_t byte_mask)
+                                                     float u_n, float inv_delta, int top_n,
+                                                     const float2 *thr_pairs, uint32_t byte_mask)
 {
     int c[4];
 #pragma unroll
@@ -151,7 +150,7 @@ __device__ __forceinline__ uint32_t dsq_requant4_thr(const float (&y)[4], const 
         float z = y[j] * sc[j];
         z = z + sh[j];
         z = fmaxf(z, relu_floor);
-        c[j] = dsq_code_thr<LINEAR>(z, l_n, u_n, inv_delta, top_n, t1, t2, t3, thr_pairs);
+        c[j] = dsq_code_thr<false>(z, l_n, u_n, inv_delta, top_n, 0.f, 0.f, 0.f, thr_pairs);
     }
     return dsq_bytes4(c[0], c[1], c[2], c[3]) & byte_mask;
 }

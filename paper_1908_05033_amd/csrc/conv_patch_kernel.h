@@ -611,7 +611,9 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
         for (int f = 0; f < PF; ++f) psum[f] = 0;
         // (l_a = 0 here: the host sends chained layers with l_a != 0 to the simple
         // kernel.  Constants are fetched four channels at a time, right before
-        // their use, to keep the register footprint of this path small.)
+        // their use, to keep the register footprint of this path small.  Lanes of tile
+        // pixels past the end compute on patch pixel 0 and are never stored; at worst
+        // they send their wave through the exact sequence once more.)
         const int top_n = (1 << a.rq_bits) - 1;
         const float relu_floor = a.rq_relu ? 0.0f : -__builtin_inff();
         const float l_n = a.rq_l, u_n = a.rq_u, inv_delta_n = a.rq_inv_delta;
@@ -677,8 +679,7 @@ __global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(OCC, O
                         const float4 s4 = *reinterpret_cast<const float4 *>(ss_lds + ol + 8 * q);
                         const float4 b4 = *reinterpret_cast<const float4 *>(ss_lds + BC + ol + 8 * q);
                         const float sc[4] = {s4.x, s4.y, s4.z, s4.w}, sh[4] = {b4.x, b4.y, b4.z, b4.w};
-                        bytes[f][q] = dsq_requant4_thr<false>(y, sc, sh, relu_floor, l_n, u_n, inv_delta_n, top_n,
-                                                              0.f, 0.f, 0.f, thr_lds, mask[q]);
+                        bytes[f][q] = dsq_requant4_thr(y, sc, sh, relu_floor, l_n, u_n, inv_delta_n, top_n, thr_lds, mask[q]);
                     }
                 }
                 const int sum = (int)__builtin_amdgcn_sad_u8(bytes[f][3], 0u, __builtin_amdgcn_sad_u8(bytes[f][2], 0u,

@@ -6,8 +6,9 @@ or ``--pmc WRITE_SIZE``):
 
 It launches (1) a plain device-to-device copy of a known size, which calibrates
 the counter (bytes the counter reports per byte really moved), and (2) the
-quantize and convolution kernels of the first layer of a config, each over
-several distinct buffer sets so that the last-level cache cannot serve them.
+quantize and convolution kernels of one layer of a config (with --chained also
+dsq_conv2d_requant), each over several distinct buffer sets so that the
+last-level cache cannot serve them.
 """
 import argparse
 
@@ -26,6 +27,7 @@ def main():
     ap.add_argument("--bits", type=int, default=None)
     ap.add_argument("--sets", type=int, default=0, help="buffer sets (0 = enough to exceed 600 MB, at most 48)")
     ap.add_argument("--many-in-flight", action="store_true", help="pass DSQ_CONV_MANY_IN_FLIGHT")
+    ap.add_argument("--chained", action="store_true", help="also launch dsq_conv2d_requant (same layer, codes out)")
     a = ap.parse_args()
     flags = B.DSQ_CONV_MANY_IN_FLIGHT if a.many_in_flight else 0
     L = inputs.config_layers(a.cfg, a.bits)[a.layer]
@@ -59,6 +61,15 @@ def main():
     for b in bufs:
         B.dsq_conv2d(b.desc, b.act_packed, b.pix_code_sum, 0.0, 2.5, wp, aux, b.out, B.DSQ_NHWC, None)
     torch.cuda.synchronize()
+    if a.chained:
+        scale = torch.rand(L.C_out, device=dev, generator=gen) + 0.5
+        shift = torch.randn(L.C_out, device=dev, generator=gen) * 0.1
+        nxt = [(torch.empty(B.dsq_act_packed_bytes(L.N, L.Ho, L.Wo, L.C_out, L.bits), dtype=torch.uint8, device=dev),
+                torch.empty(L.N * L.Ho * L.Wo, dtype=torch.int32, device=dev)) for _ in bufs]
+        for b, (codes, pix) in zip(bufs, nxt):
+            B.dsq_conv2d_requant(b.desc, b.act_packed, b.pix_code_sum, 0.0, 2.5, wp, aux, scale, shift, True, 0.0, 1.0,
+                                 L.bits, codes, pix)
+        torch.cuda.synchronize()
     print("copy_bytes", COPY_BYTES, "layer", L.name, "sets", a.sets)
 
 
