@@ -126,8 +126,8 @@ typedef enum { DSQ_PACK_CONTAINER = 0, DSQ_PACK_DENSE3 = 1 } dsq_packing;
  *   output pixels and at least 512 input channels (fully connected layers;
  *   taken automatically for those).  With 2..7 the call returns
  *   DSQ_ERR_UNSUPPORTED instead of falling back when the chosen kernel cannot
- *   take the geometry (the 256x128 tile has no dsq_conv2d_requant variant and
- *   reports the same).
+ *   take the geometry (the 256x128 tile has a dsq_conv2d_requant variant for 1- and
+ *   2-bit layers only and reports the same for the others).
  * DSQ_CONV_MANY_IN_FLIGHT tells the automatic choice that the caller keeps
  *   several calls in flight on different streams (a server with several
  *   requests, independent branches of a network): layers that yield only about

@@ -105,15 +105,15 @@ int pick_tile(const DsqConvArgs &a)
         // 2-bit layers (FP4 path: the 256x128 tile fits its registers): take that
         // tile when the 128x128 one leaves a nearly empty last round of workgroups
         // (3 per CU, 768 at a time) and the large one (2 per CU, 512) does not
-        if (a.cont == 2 && !a.rq) {
+        if (a.cont == 2) {
             const double bm = (double)blocks(kMedium), bl = (double)blocks(kLarge);
             const double waste_m = (double)((blocks(kMedium) + 767) / 768 * 768) / bm;
             const double waste_l = (double)((blocks(kLarge) + 511) / 512 * 512) / bl;
             if (bl >= 256 && waste_m > 1.35 * waste_l) return TILE_LARGE;
             // deep 3x3 layers with about one workgroup per CU (256 -> 256 at 14x14 x 64,
             // 512 -> 512 at 14x14 x 32): the 256x64 tile with one wave group measured 6-10 %
-            // ahead of the 128x128 tile with two
-            if (a.R == 3 && a.stride == 1 && a.Cp >= 256 && !a.many_in_flight && blocks(kMedium) <= 320 &&
+            // ahead of the 128x128 tile with two (plain call; the chained call measures the other way)
+            if (!a.rq && a.R == 3 && a.stride == 1 && a.Cp >= 256 && !a.many_in_flight && blocks(kMedium) <= 320 &&
                 blocks(kTall) >= 192)
                 return TILE_TALL;
         }
@@ -135,9 +135,10 @@ bool choose_plan(const DsqConvArgs &a, int force_tile, int &which, int &ks, Patc
 {
     if ((long long)a.N * a.H * a.W * (a.Cp * a.cont / 8) > 0x7FFFFFFFLL) return false;
     which = force_tile >= 0 ? force_tile : pick_tile(a);
-    // chained mode: the test-only tile has no variant, and layers with l_a != 0
-    // (border-dependent terms) go to the simple kernel
-    if (a.rq && (which == TILE_LARGE || a.l_a != 0.0f)) return false;
+    // chained mode: the 256x128 tile has a variant for 2-bit containers only (at 3 and
+    // 4 bits it does not fit the registers), and layers with l_a != 0 (border-dependent
+    // terms) go to the simple kernel
+    if (a.rq && ((which == TILE_LARGE && a.cont != 2) || a.l_a != 0.0f)) return false;
     const TileCfg &tc = tile_cfg(which);
     const int BP = 32 * tc.PF * tc.WP, BC = 32 * tc.CT * tc.WC;
     const long long M = (long long)a.N * a.Ho * a.Wo;

@@ -867,7 +867,10 @@ hipError_t dispatch_variant(const DsqConvArgs &a, const PatchPlan &pl, int which
 {
 #define DSQ_TILE(CONT, RR, UPT)                                                                \
     do {                                                                                       \
-        if (which == TILE_LARGE) return launch_kernel<CONT, RR, 2, 2, 4, 2, UPT, (RR == 3 ? 3 : 1), 2, 1, false>(a, pl, stream);  \
+        if (which == TILE_LARGE) {                                                             \
+            if constexpr (CONT == 2) return launch_cfg<CONT, RR, 2, 2, 4, 2, UPT, (RR == 3 ? 3 : 1), 2>(a, pl, stream); \
+            else return launch_kernel<CONT, RR, 2, 2, 4, 2, UPT, (RR == 3 ? 3 : 1), 2, 1, false>(a, pl, stream);  \
+        }                                                                                      \
         if (which == TILE_MEDIUM && ks == 2) return launch_cfg<CONT, RR, 2, 2, 2, 2, UPT, (RR == 3 ? 3 : 1), 2, 2>(a, pl, stream); \
         if (which == TILE_MEDIUM) return launch_cfg<CONT, RR, 2, 2, 2, 2, UPT, (RR == 3 ? 3 : 1), 3>(a, pl, stream); \
         if (which == TILE_TALL) return launch_cfg<CONT, RR, 4, 1, 2, 2, UPT, (RR == 3 ? 3 : 1), 3>(a, pl, stream); \
