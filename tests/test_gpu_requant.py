@@ -311,6 +311,67 @@ def test_values_on_and_beside_the_quantizer_steps(geom, bits, bits_n, relu, kern
     assert (inside & (d < 2e-4)).sum() > z.size // 200, "the case must put many outputs next to a step"
 
 
+SPECIAL = [0.0, -0.0, 1.0, -1.0, 1e-30, -1e-30, 1e30, -1e30, 3e38, 1e-45, -1e-45, float("inf"), -float("inf"), float("nan"),
+           2.0 ** 59, 2.0 ** 61, 2.0 ** -59, 2.0 ** -61, 2.0 ** 99, 2.0 ** 101]
+
+
+@pytest.mark.parametrize("kernel", [0, 3, 4, 6])
+@pytest.mark.parametrize("bits,bits_n,relu,l_n,u_n", [(4, 4, True, 0.0, 2.0), (2, 2, False, -1.5, 1.5), (4, 2, True, -1.0, 3.0),
+                                                       (2, 4, False, 0.0, 1e-28), (4, 4, False, -1e25, 1e25),
+                                                       (3, 3, True, 1e-3, 2e-3)])
+def test_extreme_scale_shift_and_ranges(bits, bits_n, relu, l_n, u_n, kernel):
+    """Channels whose scale or shift is zero, tiny, huge, infinite or NaN, and next
+    ranges with a tiny or a huge step: the tuned kernels must send whatever their
+    short evaluation cannot bound through the exact sequence, so that the codes equal
+    the simple kernel's bit for bit (which runs the recipe on every output)."""
+    N, Ci, H, W, Co, R, stride, pad = 2, 64, 6, 7, 2 * len(SPECIAL) * 2, 3, 1, 1
+    layer, inp = inputs.small_random_case(900 + bits, N, Ci, H, W, Co, R, stride, pad, bits, l_a=0.0, u_a=2.1)
+    sp = np.array(SPECIAL, np.float32)
+    scale = np.ones(Co, np.float32)
+    shift = np.zeros(Co, np.float32)
+    n = len(SPECIAL)
+    scale[:n] = sp                       # special scale, ordinary shift
+    shift[:n] = 0.3
+    shift[n:2 * n] = sp                  # ordinary scale, special shift
+    scale[2 * n:3 * n] = sp              # both special
+    shift[2 * n:3 * n] = sp[::-1]
+    scale[3 * n:] = 0.5                  # ordinary channels beside them
+    shift[3 * n:] = np.linspace(-1, 1, Co - 3 * n, dtype=np.float32)
+    l_n, u_n = float(np.float32(l_n)), float(np.float32(u_n))
+    ref, ref_pix, *_ = run_requant_gpu(layer, inp, scale, shift, relu, l_n, u_n, bits_n, 1)
+    got, pix, *_ = run_requant_gpu(layer, inp, scale, shift, relu, l_n, u_n, bits_n, kernel)
+    assert np.array_equal(got, ref)
+    assert np.array_equal(pix, ref_pix)
+    # and the ordinary channels agree with the oracle (the special ones too, where the oracle's
+    # float32 sequence is the same; NaN and infinities follow the recipe's clip on both sides)
+    a_code, w_code = oracle_layer(layer, inp)
+    y = oracle.conv_real(a_code, inp["l_a"], inp["u_a"], w_code, inp["l_w"], inp["u_w"], bits, stride, pad)
+    with np.errstate(all="ignore"):
+        z = oracle.affine_relu(y, scale, shift, relu)
+        want = oracle.quantize(z, l_n, u_n, bits_n)
+    ordinary = slice(3 * n, Co)
+    if u_n - l_n > 1e-3 and u_n - l_n < 1e3:
+        assert_codes_match(got[..., ordinary], want[:, ordinary], z[:, ordinary], l_n, u_n, bits_n, Co - 3 * n)
+
+
+def test_depth_beyond_the_binary32_integers():
+    """A 4-bit layer deep enough that an accumulator may pass 2^24 (225 * 9 * C_in): the
+    tuned kernels' short evaluation would convert it inexactly and is switched off by
+    the host; codes equal the simple kernel's and the oracle's."""
+    N, Ci, H, W, Co, R, stride, pad = 1, 8320, 3, 3, 64, 3, 1, 1
+    layer, inp = inputs.small_random_case(77, N, Ci, H, W, Co, R, stride, pad, 4, l_a=0.0, u_a=2.1)
+    scale, shift = inputs.affine_params(5, Co, shift_std=0.05)
+    scale = (scale * 0.02).astype(np.float32)
+    y, z, _ = oracle_requant(layer, inp, scale, shift, True, 0.0, 1.0, 4)
+    l_n, u_n = next_range(z, True)
+    want = oracle.quantize(z, l_n, u_n, 4)
+    ref, ref_pix, *_ = run_requant_gpu(layer, inp, scale, shift, True, l_n, u_n, 4, 1)
+    for kernel in (0, 3, 4):
+        got, pix, *_ = run_requant_gpu(layer, inp, scale, shift, True, l_n, u_n, 4, kernel)
+        assert np.array_equal(got, ref) and np.array_equal(pix, ref_pix)
+        assert_codes_match(got, want, z, l_n, u_n, 4, Co)
+
+
 def _oracle_threshold(l, u, bits, j):
     """Smallest float32 whose oracle code is >= j (bisection over the ordered floats)."""
     def key(x):
