@@ -289,7 +289,17 @@ def main():
         return
     tot_t, tot_macs = 0.0, 0
     for L in layers:
-        r = bench_layer(L, kernel=a.kernel, many_in_flight=a.many_in_flight, chained=a.chained, dense3=a.dense3)
+        try:
+            r = bench_layer(L, kernel=a.kernel, many_in_flight=a.many_in_flight, chained=a.chained, dense3=a.dense3)
+        except B.DsqError as e:
+            if e.status != 5 or a.kernel < 2:
+                raise
+            # a forced tile that does not take this layer (or has no chained variant for it)
+            try:
+                r = bench_layer(L, kernel=a.kernel, many_in_flight=a.many_in_flight, chained=False, dense3=a.dense3)
+            except B.DsqError:
+                print(json.dumps({"layer_skipped": L.name, "reason": "kernel %d does not take it" % a.kernel}), flush=True)
+                continue
         print(json.dumps(r), flush=True)
         tot_t += (r["conv_us"] + r["quant_us"]) * 1e-6 * L.count
         tot_macs += L.macs * L.count
