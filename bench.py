@@ -297,6 +297,20 @@ def main():
                 "quant_plus_conv_ms": round(tot_t * 1e3, 4), "TOPS": round(2.0 * tot_macs / tot_t / 1e12, 1),
                 "timing": "sum of per-kernel times, each kernel alone, buffer sets rotating over > 600 MB (cold)",
                 "layers": lrows}
+        # the four single-image 3x3 layers whose ARM timings the paper prints (Sec. 4.5, Table 8: stride
+        # and padding are not stated there; 1 and 1 assumed).  Context, measured the same way: one image is
+        # a few microseconds of launch and memory latency on this machine, not a throughput workload.
+        paper_ms = {"64x56x56": (43.80, 40.06, 38.11), "128x28x28": (33.89, 29.94, 28.15),
+                    "256x14x14": (37.03, 31.16, 29.20), "512x7x7": (30.20, 26.14, 25.43)}
+        t8 = []
+        for (c, hw), ms in zip(((64, 56), (128, 28), (256, 14), (512, 7)), paper_ms.values()):
+            for b, ms_b in zip((4, 3, 2), ms):
+                L = inputs.ConvLayer("table8.%dx%dx%d" % (c, hw, hw), 1, c, hw, hw, c, 3, 3, 1, 1, b)
+                r = LB.bench_layer(L, reps=3)
+                t8.append({"layer": L.name, "bits": b, "conv_us": r["conv_us"], "quant_us": r["quant_us"],
+                           "paper_arm_single_thread_ms": ms_b})
+                torch.cuda.empty_cache()
+        other["paper_table8_shapes_one_image"] = t8
         result["other_workloads"] = other
 
     if not args.no_cpu_baseline:
